@@ -1,0 +1,153 @@
+/*
+ * lutgemm.h -- C ABI of the MI355X (gfx950) LUT-GEMM library.
+ *
+ * The library computes the weight-only-quantised product
+ *
+ *      y[b][r] = sum_{k<n} What[r][k] * x[b][k]
+ *      What[r][k] = sum_{i<q} alpha[i][r][G(k)] * B_i[r][k]  +  z[r][G(k)],   G(k) = k / g
+ *
+ * with B_i in {-1,+1} (binary-coding quantisation, paper section 2.3; bias-extended
+ * form, section 3.3 eq. 3; one scale per group of g input columns, section 3.4).
+ * The product is evaluated the way section 3.1 describes: every run of mu = 8
+ * activations becomes a 2^mu-entry table of signed partial sums, and mu packed weight
+ * bits, read as one byte, index that table. Nothing is dequantised.
+ *
+ * Conventions shared by every entry point
+ *   - Return value: LUTGEMM_OK (0) or a negative LUTGEMM_E* code. Nothing throws,
+ *     aborts, allocates device memory or synchronises a stream.
+ *   - The caller owns every buffer, before and after the call.
+ *   - "fp16" is IEEE binary16 carried as uint16_t.
+ *   - g == 0 means row-wise quantisation (g = n).
+ *   - Required: 1 <= q <= 8, mu == 8, m >= 1, n >= 8, n % 8 == 0, g % 8 == 0,
+ *     n % g == 0. Anything else is LUTGEMM_EINVAL (malformed) or
+ *     LUTGEMM_EUNSUPPORTED (well-formed, not implemented: mu != 8, batch > 32).
+ *
+ * ---------------------------------------------------------------------------------
+ * Packed ("device") layouts.  These are a contract: lutgemm_pack_bcq writes them,
+ * the kernels read them, and an independent decoder can be written from this text.
+ *
+ * Notation: chunk c = k / 8 (n/8 chunks per row); the key of (plane i, row r, chunk c)
+ * is the byte whose bit j (LSB = bit 0) is 1 iff B_i[r][8c + j] = +1  (section 3.1:
+ * a key is mu concatenated binary elements; polarity and bit order are this
+ * library's choice).  Row block rb = r / 16, rho = r % 16, RB = ceil(m / 16).
+ * K tile kt = c / 128, NT = ceil((n/8) / 128).  Tile kt holds
+ * C = min(128, n/8 - 128*kt) chunks and has T = 2 sub-slabs if C > 64, else T = 1
+ * (only the last tile can have C < 128).  Slot (t, L), t < T, L < 64, of tile kt
+ * stands for chunk 128*kt + T*L + t.
+ *
+ *   bits   one byte per (plane, row, chunk):
+ *            offset = kt * RB * q * 2048
+ *                   + ((rb * q + i) * T + t) * 1024 + L * 16 + rho
+ *          Bytes of rows >= m and of slots whose chunk >= n/8 are 0.
+ *          Size = RB * q * 1024 * (2 * (NT - 1) + T_last) bytes, which equals
+ *          m*n*q/8 (the binary-weight term of section 3.4 eq. 4) when m % 16 == 0
+ *          and n % 512 == 0.
+ *   alpha  fp16, one per (plane, row, group), NG = n / g groups:
+ *            index = ((rb * NG + G) * q + i) * 16 + rho
+ *          Rows >= m hold 0.  Size = RB * NG * q * 32 bytes ( = 2*m*(n/g)*q, the
+ *          scale term of eq. 4, when m % 16 == 0).
+ *   z      fp16, one per (row, group):  index = (rb * NG + G) * 16 + rho.
+ *          Rows >= m hold 0.  Size = RB * NG * 32 bytes.
+ * ---------------------------------------------------------------------------------
+ */
+#ifndef LUTGEMM_H
+#define LUTGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  LUTGEMM_OK = 0,
+  LUTGEMM_EINVAL = -1,       /* null pointer, size out of range, n % 8, n % g, g % 8, misaligned pointer */
+  LUTGEMM_EUNSUPPORTED = -2, /* mu != 8, batch > 32, unknown mode or flag */
+  LUTGEMM_EWORKSPACE = -3,   /* workspace_bytes < lutgemm_workspace_bytes(...) */
+  LUTGEMM_EHIP = -4          /* a HIP call failed; the HIP error is left for hipGetLastError */
+};
+
+/* Quantiser selected by lutgemm_pack_bcq's `mode`. */
+enum {
+  /* Symmetric greedy BCQ (section 2.3 format). Per (row, group), residual r0 = w (fp32):
+     plane i: B_i = sign(r_i) with sign(0) = +1; alpha_i = fp16(mean_k |r_i[k]|), the mean
+     being an fp64 sum in increasing k divided by g, rounded once to fp16 (nearest even);
+     r_{i+1} = r_i - alpha_i * B_i in fp32 using the rounded alpha_i.  No offset.        */
+  LUTGEMM_Q_GREEDY = 0,
+  /* As above on w - z, with z = fp16(mean_k w[k]) (same fp64 sum, one rounding); the
+     asymmetric format of section 3.3 eq. 3.                                              */
+  LUTGEMM_Q_GREEDY_MEAN_OFFSET = 1,
+  /* Asymmetric min/max round-to-nearest uniform quantisation converted to BCQ as in
+     appendix C: zhat = min, s = fp16((max - min) / (2^q - 1)) (fp32 arithmetic, one
+     rounding), u = clamp(rint((w - zhat) / s), 0, 2^q - 1) in fp32, plane i = bit i of u,
+     alpha_i = fp16(2^(i-1) * s), z = fp16(zhat + sum_i alpha_i) (fp32 sum over the stored
+     alpha_i, i ascending, then + zhat).  If s == 0 every bit is 1, alpha_i = 0, z = zhat. */
+  LUTGEMM_Q_UNIFORM_RTN = 2
+};
+
+/* `flags` of lutgemm_gemv / lutgemm_gemm. */
+enum {
+  LUTGEMM_Y_F16 = 0, /* y is fp16, rounded to nearest even from the fp32 sum (paper table 1: FP16 output) */
+  LUTGEMM_Y_F32 = 1  /* y is fp32 */
+};
+
+/* Buffer sizes in bytes of the packed layouts above (section 3.4 eq. 4, padded to the
+   tile grid).  Return 0 for arguments that violate the requirements at the top.        */
+size_t lutgemm_bits_bytes(int64_t m, int64_t n, int q);
+size_t lutgemm_alpha_bytes(int64_t m, int64_t n, int q, int g);
+size_t lutgemm_z_bytes(int64_t m, int64_t n, int g);
+
+/* Device scratch a gemv/gemm call needs (split-K partial sums: the per-tile partial
+   outputs that appendix B accumulates across thread blocks).  0 on invalid arguments.  */
+size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch);
+
+/* HOST.  Quantise W (fp16, row-major m x n, host memory) to q planes with group size g
+   using `mode`, and write the packed layouts into host buffers of the sizes above.
+   z_out must be non-null for the two offset modes and may be null for LUTGEMM_Q_GREEDY
+   (if non-null it is filled with zeros).  Deterministic: same input, same bytes.
+   Format: section 2.3, section 3.3 eq. 3, appendix C.                                   */
+int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int mu, int mode,
+                     void* bits_out, uint16_t* alpha_out, uint16_t* z_out);
+
+/* HOST.  Decode packed bits back to B_pm1[q][m][n] in {-1,+1} (int8, host memory).      */
+int lutgemm_unpack_bcq(const void* bits, int64_t m, int64_t n, int q, int mu, int8_t* B_pm1);
+
+/* HOST.  Write already-known planes B_pm1[q][m][n] (entries -1/+1) in the packed bits
+   layout; used when a quantiser outside this library produced the planes (appendix C:
+   integer weights of any uniform quantiser turned into binary weights).                 */
+int lutgemm_pack_planes(const int8_t* B_pm1, int64_t m, int64_t n, int q, int mu, void* bits_out);
+
+/* HOST.  Reorder canonical scales alpha[q][m][NG] (and offsets z[m][NG], nullable pair)
+   into the packed alpha / z layouts.                                                    */
+int lutgemm_pack_scales(const uint16_t* alpha, const uint16_t* z, int64_t m, int64_t n, int q, int g,
+                        uint16_t* alpha_out, uint16_t* z_out);
+
+/* DEVICE pointers, all 16-byte aligned.  y = What * x for one activation vector
+   (section 3.2: y = sum_i A_i o (B_i . x); offset term from eq. 3).
+     x      fp16 [n]                       bits, alpha, z   packed layouts above (z nullable)
+     y      fp16 [m] or fp32 [m] (flags); overwritten, never read
+     workspace  at least lutgemm_workspace_bytes(m, n, q, g, mu, 1) bytes; contents
+                need not be initialised and are undefined afterwards
+     hip_stream a hipStream_t (NULL = the null stream); the work is enqueued and the call
+                returns without waiting.  Calls that share a workspace must be ordered on
+                one stream.
+   The result is bitwise reproducible from run to run.                                   */
+int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                 int q, int g, int mu, int64_t m, int64_t n, unsigned flags,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* As lutgemm_gemv for `batch` activation vectors (1 <= batch <= 32): x is fp16
+   [batch][n], y is [batch][m]; one table set per activation vector, each fetched key
+   serving all of them (the small-batch case discussed in section 6).                    */
+int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                 int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Human-readable name of an error code (static storage).                                */
+const char* lutgemm_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LUTGEMM_H */
