@@ -65,7 +65,7 @@ enum {
   LUTGEMM_EINVAL = -1,       /* null pointer, size out of range, n % 8, n % g, g % 8, misaligned pointer */
   LUTGEMM_EUNSUPPORTED = -2, /* mu != 8, batch > 32, unknown mode or flag */
   LUTGEMM_EWORKSPACE = -3,   /* workspace_bytes < lutgemm_workspace_bytes(...) */
-  LUTGEMM_EHIP = -4          /* a HIP call failed; the HIP error is left for hipGetLastError */
+  LUTGEMM_EHIP = -4          /* a HIP runtime call (device query, kernel launch) returned an error */
 };
 
 /* Quantiser selected by lutgemm_pack_bcq's `mode`. */

@@ -1,0 +1,335 @@
+// Host side of the LUT-GEMM library: buffer sizes, the BCQ quantisers and the packing of
+// planes / scales / offsets into the layouts that include/lutgemm.h specifies.
+// Formats: paper section 2.3 (BCQ), section 3.3 eq. 3 (offset), appendix C (uniform to
+// BCQ), section 3.4 eq. 4 (sizes).  Nothing here touches the GPU.
+#include "lutgemm.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+namespace {
+
+constexpr int kRowsPerBlock = 16;    // rows whose keys share one 16-byte lane word
+constexpr int kChunksPerTile = 128;  // 1024 input columns per K tile
+constexpr int kSlabBytes = 1024;     // 64 lanes x 16 rows, one plane, one sub-slab
+
+struct Shape {
+  int64_t m, n, RB, nchunks, NT, NG, g;
+  int q;
+};
+
+bool make_shape(int64_t m, int64_t n, int q, int g, Shape* s) {
+  if (m < 1 || n < 8 || n % 8 != 0 || q < 1 || q > 8 || g < 0) return false;
+  int64_t gg = g == 0 ? n : g;
+  if (gg % 8 != 0 || n % gg != 0) return false;
+  s->m = m;
+  s->n = n;
+  s->q = q;
+  s->g = gg;
+  s->RB = (m + kRowsPerBlock - 1) / kRowsPerBlock;
+  s->nchunks = n / 8;
+  s->NT = (s->nchunks + kChunksPerTile - 1) / kChunksPerTile;
+  s->NG = n / gg;
+  return true;
+}
+
+inline int tile_T(const Shape& s, int64_t kt) {
+  int64_t C = std::min<int64_t>(kChunksPerTile, s.nchunks - kt * kChunksPerTile);
+  return C > 64 ? 2 : 1;
+}
+
+// Per-chunk part of the key offset: tile base + sub-slab + lane, and the tile's T.
+struct ChunkSlot {
+  int64_t base;  // kt*RB*q*2048 + t*1024 + L*16
+  int T;
+};
+
+std::vector<ChunkSlot> chunk_slots(const Shape& s) {
+  std::vector<ChunkSlot> v(s.nchunks);
+  for (int64_t c = 0; c < s.nchunks; ++c) {
+    int64_t kt = c / kChunksPerTile;
+    int T = tile_T(s, kt);
+    int64_t cc = c - kt * kChunksPerTile;
+    int64_t L = cc / T, t = cc % T;
+    v[c].base = kt * s.RB * s.q * 2 * kSlabBytes + t * kSlabBytes + L * 16;
+    v[c].T = T;
+  }
+  return v;
+}
+
+inline int64_t key_offset(const Shape& s, const ChunkSlot& cs, int i, int64_t r) {
+  int64_t rb = r / kRowsPerBlock, rho = r % kRowsPerBlock;
+  return cs.base + (rb * s.q + i) * cs.T * kSlabBytes + rho;
+}
+
+size_t bits_bytes(const Shape& s) {
+  return (size_t)s.RB * s.q * kSlabBytes * (2 * (s.NT - 1) + tile_T(s, s.NT - 1));
+}
+
+inline float half_to_float(uint16_t h) {
+  uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+  uint32_t e = (h >> 10) & 0x1f, f = h & 0x3ffu, bits;
+  if (e == 0) {
+    if (f == 0) {
+      bits = sign;
+    } else {  // subnormal: renormalise
+      int sh = 0;
+      while (!(f & 0x400u)) {
+        f <<= 1;
+        ++sh;
+      }
+      bits = sign | ((uint32_t)(113 - sh) << 23) | ((f & 0x3ffu) << 13);
+    }
+  } else if (e == 31) {
+    bits = sign | 0x7f800000u | (f << 13);
+  } else {
+    bits = sign | ((e + 112) << 23) | (f << 13);
+  }
+  float out;
+  std::memcpy(&out, &bits, 4);
+  return out;
+}
+
+// double -> binary16, one rounding, nearest even (the default rounding mode is assumed).
+inline uint16_t double_to_half(double d) {
+  uint16_t sign = std::signbit(d) ? 0x8000u : 0;
+  double x = std::fabs(d);
+  if (std::isnan(x)) return sign | 0x7e00u;
+  if (x >= 65520.0) return sign | 0x7c00u;
+  if (x < 6.103515625e-05) {  // below the smallest normal: multiples of 2^-24
+    return sign | (uint16_t)std::nearbyint(std::ldexp(x, 24));
+  }
+  int e;
+  std::frexp(x, &e);                                       // x = f * 2^e, f in [0.5, 1)
+  double mant = std::nearbyint(std::ldexp(x, 11 - e));     // in [1024, 2048]
+  int be = e - 1 + 15;
+  if (mant == 2048.0) {
+    mant = 1024.0;
+    ++be;
+  }
+  return sign | (uint16_t)((be << 10) | ((int)mant - 1024));
+}
+
+template <class F>
+void parallel_blocks(int64_t nblocks, F&& fn) {
+  unsigned hw = std::thread::hardware_concurrency();
+  int64_t nt = std::max<int64_t>(1, std::min<int64_t>(hw ? hw : 1, std::min<int64_t>(nblocks, 64)));
+  if (nt == 1) {
+    fn(0, nblocks);
+    return;
+  }
+  std::vector<std::thread> th;
+  for (int64_t t = 0; t < nt; ++t) {
+    int64_t b0 = nblocks * t / nt, b1 = nblocks * (t + 1) / nt;
+    th.emplace_back([=, &fn] { fn(b0, b1); });
+  }
+  for (auto& t : th) t.join();
+}
+
+// fp64 sum in increasing index order.
+inline double seq_sum_abs(const float* r, int64_t g) {
+  double s = 0.0;
+  for (int64_t k = 0; k < g; ++k) s += std::fabs((double)r[k]);
+  return s;
+}
+inline double seq_sum(const float* r, int64_t g) {
+  double s = 0.0;
+  for (int64_t k = 0; k < g; ++k) s += (double)r[k];
+  return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lutgemm_bits_bytes(int64_t m, int64_t n, int q) {
+  Shape s;
+  if (!make_shape(m, n, q, 0, &s)) return 0;
+  return bits_bytes(s);
+}
+
+size_t lutgemm_alpha_bytes(int64_t m, int64_t n, int q, int g) {
+  Shape s;
+  if (!make_shape(m, n, q, g, &s)) return 0;
+  return (size_t)s.RB * s.NG * q * kRowsPerBlock * 2;
+}
+
+size_t lutgemm_z_bytes(int64_t m, int64_t n, int g) {
+  Shape s;
+  if (!make_shape(m, n, 1, g, &s)) return 0;
+  return (size_t)s.RB * s.NG * kRowsPerBlock * 2;
+}
+
+size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch) {
+  Shape s;
+  if (mu != 8 || batch < 1 || batch > 32 || !make_shape(m, n, q, g, &s)) return 0;
+  // one fp32 partial per (K tile, activation vector, padded row)
+  return (size_t)s.NT * batch * s.RB * kRowsPerBlock * sizeof(float);
+}
+
+int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int mu, int mode,
+                     void* bits_out, uint16_t* alpha_out, uint16_t* z_out) {
+  Shape s;
+  if (!W || !bits_out || !alpha_out) return LUTGEMM_EINVAL;
+  if (!make_shape(m, n, q, g, &s)) return LUTGEMM_EINVAL;
+  if (mu != 8) return LUTGEMM_EUNSUPPORTED;
+  if (mode != LUTGEMM_Q_GREEDY && mode != LUTGEMM_Q_GREEDY_MEAN_OFFSET && mode != LUTGEMM_Q_UNIFORM_RTN)
+    return LUTGEMM_EUNSUPPORTED;
+  const bool has_offset = mode != LUTGEMM_Q_GREEDY;
+  if (has_offset && !z_out) return LUTGEMM_EINVAL;
+
+  uint8_t* bits = static_cast<uint8_t*>(bits_out);
+  std::memset(bits, 0, bits_bytes(s));
+  std::memset(alpha_out, 0, lutgemm_alpha_bytes(m, n, q, g));
+  if (z_out) std::memset(z_out, 0, lutgemm_z_bytes(m, n, g));
+  const std::vector<ChunkSlot> slots = chunk_slots(s);
+  const int64_t G = s.g, cpg = G / 8;
+
+  parallel_blocks(s.RB, [&](int64_t rb0, int64_t rb1) {
+    std::vector<float> res(G);
+    std::vector<int> code(G);
+    for (int64_t r = rb0 * kRowsPerBlock; r < std::min<int64_t>(m, rb1 * kRowsPerBlock); ++r) {
+      const int64_t rb = r / kRowsPerBlock, rho = r % kRowsPerBlock;
+      for (int64_t gi = 0; gi < s.NG; ++gi) {
+        const uint16_t* w = W + r * n + gi * G;
+        for (int64_t k = 0; k < G; ++k) res[k] = half_to_float(w[k]);
+        uint16_t* a_dst = alpha_out + ((rb * s.NG + gi) * q) * kRowsPerBlock + rho;
+        uint16_t* z_dst = z_out ? z_out + (rb * s.NG + gi) * kRowsPerBlock + rho : nullptr;
+
+        if (mode == LUTGEMM_Q_UNIFORM_RTN) {
+          float lo = res[0], hi = res[0];
+          for (int64_t k = 1; k < G; ++k) {
+            lo = std::min(lo, res[k]);
+            hi = std::max(hi, res[k]);
+          }
+          const float levels = (float)((1 << q) - 1);
+          const float range_step = (hi - lo) / levels;
+          const uint16_t s16 = double_to_half((double)range_step);
+          const float sf = half_to_float(s16);
+          for (int64_t k = 0; k < G; ++k) {
+            if (sf == 0.0f) {
+              code[k] = (1 << q) - 1;
+            } else {
+              float u = std::nearbyint((res[k] - lo) / sf);
+              u = std::min(std::max(u, 0.0f), levels);
+              code[k] = (int)u;
+            }
+          }
+          float zsum = 0.0f;
+          for (int i = 0; i < q; ++i) {
+            const uint16_t a16 = double_to_half((double)(std::ldexp(1.0f, i - 1) * sf));
+            a_dst[i * kRowsPerBlock] = a16;
+            zsum = zsum + half_to_float(a16);
+            for (int64_t c = 0; c < cpg; ++c) {
+              unsigned key = 0;
+              for (int j = 0; j < 8; ++j) key |= (unsigned)((code[c * 8 + j] >> i) & 1) << j;
+              bits[key_offset(s, slots[gi * cpg + c], i, r)] = (uint8_t)key;
+            }
+          }
+          *z_dst = double_to_half((double)(zsum + lo));
+          continue;
+        }
+
+        if (mode == LUTGEMM_Q_GREEDY_MEAN_OFFSET) {
+          const uint16_t z16 = double_to_half(seq_sum(res.data(), G) / (double)G);
+          *z_dst = z16;
+          const float zf = half_to_float(z16);
+          for (int64_t k = 0; k < G; ++k) res[k] = res[k] - zf;
+        }
+        for (int i = 0; i < q; ++i) {
+          const uint16_t a16 = double_to_half(seq_sum_abs(res.data(), G) / (double)G);
+          a_dst[i * kRowsPerBlock] = a16;
+          const float af = half_to_float(a16);
+          for (int64_t c = 0; c < cpg; ++c) {
+            unsigned key = 0;
+            for (int j = 0; j < 8; ++j) {
+              float& rv = res[c * 8 + j];
+              if (rv >= 0.0f) {  // sign(0) = +1
+                key |= 1u << j;
+                rv = rv - af;
+              } else {
+                rv = rv + af;
+              }
+            }
+            bits[key_offset(s, slots[gi * cpg + c], i, r)] = (uint8_t)key;
+          }
+        }
+      }
+    }
+  });
+  return LUTGEMM_OK;
+}
+
+int lutgemm_unpack_bcq(const void* bits_in, int64_t m, int64_t n, int q, int mu, int8_t* B_pm1) {
+  Shape s;
+  if (!bits_in || !B_pm1 || !make_shape(m, n, q, 0, &s)) return LUTGEMM_EINVAL;
+  if (mu != 8) return LUTGEMM_EUNSUPPORTED;
+  const uint8_t* bits = static_cast<const uint8_t*>(bits_in);
+  const std::vector<ChunkSlot> slots = chunk_slots(s);
+  parallel_blocks(s.RB, [&](int64_t rb0, int64_t rb1) {
+    for (int i = 0; i < q; ++i)
+      for (int64_t r = rb0 * kRowsPerBlock; r < std::min<int64_t>(m, rb1 * kRowsPerBlock); ++r) {
+        int8_t* dst = B_pm1 + ((int64_t)i * m + r) * n;
+        for (int64_t c = 0; c < s.nchunks; ++c) {
+          unsigned key = bits[key_offset(s, slots[c], i, r)];
+          for (int j = 0; j < 8; ++j) dst[c * 8 + j] = ((key >> j) & 1) ? 1 : -1;
+        }
+      }
+  });
+  return LUTGEMM_OK;
+}
+
+int lutgemm_pack_planes(const int8_t* B_pm1, int64_t m, int64_t n, int q, int mu, void* bits_out) {
+  Shape s;
+  if (!bits_out || !B_pm1 || !make_shape(m, n, q, 0, &s)) return LUTGEMM_EINVAL;
+  if (mu != 8) return LUTGEMM_EUNSUPPORTED;
+  uint8_t* bits = static_cast<uint8_t*>(bits_out);
+  std::memset(bits, 0, bits_bytes(s));
+  const std::vector<ChunkSlot> slots = chunk_slots(s);
+  parallel_blocks(s.RB, [&](int64_t rb0, int64_t rb1) {
+    for (int i = 0; i < q; ++i)
+      for (int64_t r = rb0 * kRowsPerBlock; r < std::min<int64_t>(m, rb1 * kRowsPerBlock); ++r) {
+        const int8_t* src = B_pm1 + ((int64_t)i * m + r) * n;
+        for (int64_t c = 0; c < s.nchunks; ++c) {
+          unsigned key = 0;
+          for (int j = 0; j < 8; ++j) key |= (unsigned)(src[c * 8 + j] > 0) << j;
+          bits[key_offset(s, slots[c], i, r)] = (uint8_t)key;
+        }
+      }
+  });
+  return LUTGEMM_OK;
+}
+
+int lutgemm_pack_scales(const uint16_t* alpha, const uint16_t* z, int64_t m, int64_t n, int q, int g,
+                        uint16_t* alpha_out, uint16_t* z_out) {
+  Shape s;
+  if (!alpha || !alpha_out || !make_shape(m, n, q, g, &s)) return LUTGEMM_EINVAL;
+  if ((z == nullptr) != (z_out == nullptr)) return LUTGEMM_EINVAL;
+  std::memset(alpha_out, 0, lutgemm_alpha_bytes(m, n, q, g));
+  if (z_out) std::memset(z_out, 0, lutgemm_z_bytes(m, n, g));
+  for (int64_t r = 0; r < m; ++r) {
+    const int64_t rb = r / kRowsPerBlock, rho = r % kRowsPerBlock;
+    for (int64_t gi = 0; gi < s.NG; ++gi) {
+      for (int i = 0; i < q; ++i)
+        alpha_out[((rb * s.NG + gi) * q + i) * kRowsPerBlock + rho] = alpha[((int64_t)i * m + r) * s.NG + gi];
+      if (z) z_out[(rb * s.NG + gi) * kRowsPerBlock + rho] = z[r * s.NG + gi];
+    }
+  }
+  return LUTGEMM_OK;
+}
+
+const char* lutgemm_strerror(int code) {
+  switch (code) {
+    case LUTGEMM_OK: return "ok";
+    case LUTGEMM_EINVAL: return "invalid argument";
+    case LUTGEMM_EUNSUPPORTED: return "unsupported configuration";
+    case LUTGEMM_EWORKSPACE: return "workspace too small";
+    case LUTGEMM_EHIP: return "HIP call failed";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

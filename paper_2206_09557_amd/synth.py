@@ -14,14 +14,27 @@ OPT_175B = {"qkv": (36864, 12288), "out": (12288, 12288), "fc1": (49152, 12288),
 LLAMA_65B = {"qkv": (24576, 8192), "out": (8192, 8192), "gate_up": (22016, 8192), "down": (8192, 22016)}
 
 
-def weights_fp16(m, n, seed, std=0.02):
-    """W fp16 [m][n], iid N(0, std); drawn in fp32 in row blocks to bound host memory."""
-    rng = np.random.default_rng(seed)
+def weights_fp16(m, n, seed, std=0.02, workers=8):
+    """W fp16 [m][n], iid N(0, std).  Row blocks of a fixed size are drawn in fp32 from
+    child streams of `seed`, so the matrix does not depend on the number of workers."""
     W = np.empty((m, n), dtype=np.float16)
-    step = max(1, (1 << 24) // n)
-    for r0 in range(0, m, step):
+    step = max(1, (1 << 22) // n)
+    starts = list(range(0, m, step))
+    children = np.random.SeedSequence(seed).spawn(len(starts))
+
+    def fill(idx):
+        r0 = starts[idx]
         r1 = min(m, r0 + step)
+        rng = np.random.default_rng(children[idx])
         W[r0:r1] = (rng.standard_normal((r1 - r0, n), dtype=np.float32) * np.float32(std)).astype(np.float16)
+
+    if len(starts) == 1 or workers <= 1:
+        for i in range(len(starts)):
+            fill(i)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(fill, range(len(starts))))
     return W
 
 

@@ -1,0 +1,77 @@
+"""Helpers of the GPU parity tests: upload packed buffers with torch (device memory and
+streams only), call the C ABI through the ctypes binding, compare with the oracle."""
+import numpy as np
+
+import paper_2206_09557_amd as L
+
+
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+class Packed:
+    """Packed host buffers of one layer plus their device copies."""
+
+    def __init__(self, bits, alpha, z, m, n, q, g):
+        torch = torch_cuda()
+        self.m, self.n, self.q, self.g = m, n, q, g
+        self.bits, self.alpha, self.z = bits, alpha, z
+        self.d_bits = torch.from_numpy(bits).cuda()
+        self.d_alpha = torch.from_numpy(alpha.view(np.int16)).cuda()
+        self.d_z = None if z is None else torch.from_numpy(z.view(np.int16)).cuda()
+
+    @classmethod
+    def from_weights(cls, W, q, g, mode=L.LUTGEMM_Q_GREEDY):
+        bits, alpha, z = L.lutgemm_pack_bcq(W, q, g, mode=mode)
+        return cls(bits, alpha, z, W.shape[0], W.shape[1], q, g)
+
+
+def run(packed, x16, f32_out=False, stream=None, poison=True):
+    """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x) for the packed layer."""
+    torch = torch_cuda()
+    p = packed
+    x16 = np.ascontiguousarray(x16, dtype=np.float16)
+    batch = 1 if x16.ndim == 1 else x16.shape[0]
+    d_x = torch.from_numpy(x16.view(np.int16)).cuda()
+    ydt = torch.float32 if f32_out else torch.float16
+    d_y = torch.empty((batch, p.m), dtype=ydt, device="cuda")
+    wsb = L.lutgemm_workspace_bytes(p.m, p.n, p.q, p.g, 8, batch)
+    d_ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    if poison:          # y and the workspace must be fully overwritten, never read
+        d_y.fill_(float("nan"))
+        d_ws.fill_(0xFF)
+    s = torch.cuda.current_stream() if stream is None else stream
+    flags = L.LUTGEMM_Y_F32 if f32_out else L.LUTGEMM_Y_F16
+    torch.cuda.synchronize()
+    if x16.ndim == 1:
+        L.lutgemm_gemv(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, flags, d_ws, wsb, s.cuda_stream)
+    else:
+        L.lutgemm_gemm(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws, wsb,
+                       s.cuda_stream)
+    s.synchronize()
+    y = d_y.cpu().numpy()
+    return y[0] if x16.ndim == 1 else y
+
+
+def row_l1_bound(alpha, z, g_cols):
+    """Per-row bound sum_G g * (sum_i alpha[i][r][G] + |z[r][G]|) >= ||What_r||_1."""
+    s = np.abs(alpha.astype(np.float64)).sum(axis=0)
+    if z is not None:
+        s = s + np.abs(z.astype(np.float64))
+    return g_cols * s.sum(axis=1)
+
+
+def check_parity(y_gpu, y_ref, x16, rowbound, f32_out=False):
+    """The benchmark spec tolerances: relative L2 <= 1e-3 and max abs <= 1e-2 * |x|_inf * sum(alpha),
+    the sum read per row as a bound on the row's L1 norm; fp32 output is held to 1e-5."""
+    y_gpu = np.asarray(y_gpu, dtype=np.float64)
+    assert np.all(np.isfinite(y_gpu))
+    rel = np.linalg.norm(y_gpu - y_ref) / max(np.linalg.norm(y_ref), 1e-30)
+    assert rel <= (1e-5 if f32_out else 1e-3), f"relative L2 error {rel}"
+    xinf = float(np.abs(np.asarray(x16, dtype=np.float64)).max())
+    bound = 1e-2 * xinf * rowbound
+    bad = np.abs(y_gpu - y_ref) > bound + 1e-30
+    assert not bad.any(), f"max-abs bound broken at rows {np.flatnonzero(bad)[:8]}"
+    return rel

@@ -1,0 +1,137 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, its size helpers follow section 3.4 eq. 4, argument validation returns error
+codes without touching the GPU, and lutgemm_pack_bcq is bit-exact against the oracle's
+independent quantiser + encoder."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2206_09557_amd as L
+from oracle import bcq_oracle as O
+from paper_2206_09557_amd import synth
+from test_oracle_format import _load_layout_cases, layout_case_planes
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "lutgemm.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(lutgemm_[a-z_0-9]+)\s*\(", body))
+    assert declared == set(L.EXPORTS), declared ^ set(L.EXPORTS)
+    handle = ctypes.CDLL(L.LIB_PATH)
+    for name in declared:
+        assert getattr(handle, name) is not None
+
+
+def test_size_helpers_follow_eq4():
+    for (m, n) in list(synth.OPT_175B.values()) + list(synth.OPT_13B.values()) + list(synth.LLAMA_65B.values()):
+        for q in (2, 3, 4):
+            assert L.lutgemm_bits_bytes(m, n, q) == m * n * q // 8
+            for g in (32, 64, 128, 0):
+                ng = 1 if g == 0 else n // g
+                assert L.lutgemm_alpha_bytes(m, n, q, g) == 2 * m * ng * q
+                assert L.lutgemm_z_bytes(m, n, g) == 2 * m * ng
+                # the two terms of eq. 4, in bits
+                assert 8 * (L.lutgemm_bits_bytes(m, n, q) + L.lutgemm_alpha_bytes(m, n, q, g)) == \
+                    O.footprint_bits(m, n, q, n if g == 0 else g)
+    # padded shapes agree with the oracle's reading of the layout text
+    for (m, n, q) in [(1, 8, 1), (17, 520, 3), (33, 1544, 2), (50, 1536, 8)]:
+        assert L.lutgemm_bits_bytes(m, n, q) == O.bits_nbytes(m, n, q)
+    # invalid shapes give 0
+    assert L.lutgemm_bits_bytes(16, 12, 3) == 0 and L.lutgemm_bits_bytes(16, 64, 9) == 0
+    assert L.lutgemm_alpha_bytes(16, 64, 3, 24) == 0 and L.lutgemm_alpha_bytes(16, 64, 3, 12) == 0
+    assert L.lutgemm_workspace_bytes(16, 64, 3, 64, mu=4) == 0
+    assert L.lutgemm_workspace_bytes(16, 64, 3, 64, batch=33) == 0
+    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128) == 12 * 49152 * 4
+
+
+@pytest.mark.parametrize("m,n,q,g,mode", [
+    (17, 1544, 3, 8, L.LUTGEMM_Q_GREEDY), (33, 2048, 4, 128, L.LUTGEMM_Q_GREEDY_MEAN_OFFSET),
+    (16, 1536, 2, 64, L.LUTGEMM_Q_UNIFORM_RTN), (50, 520, 3, 0, L.LUTGEMM_Q_GREEDY),
+    (64, 1024, 3, 128, L.LUTGEMM_Q_UNIFORM_RTN), (5, 64, 8, 32, L.LUTGEMM_Q_UNIFORM_RTN),
+    (128, 1024, 3, 128, L.LUTGEMM_Q_GREEDY), (3, 8, 1, 8, L.LUTGEMM_Q_GREEDY_MEAN_OFFSET)])
+def test_pack_bcq_is_bit_exact_against_oracle(m, n, q, g, mode):
+    W = synth.weights_fp16(m, n, seed=100 + m + n)
+    if mode == L.LUTGEMM_Q_UNIFORM_RTN and m > 4:
+        W[3, :] = W[3, 0]                      # a constant row: degenerate groups
+    W[0, :8] = 0                               # exact zeros: sign(0) = +1
+    bits, alpha, z = L.lutgemm_pack_bcq(W, q, g, mode=mode)
+    if mode == L.LUTGEMM_Q_UNIFORM_RTN:
+        B, a, zz = O.quantize_uniform_rtn(W, q, g)
+    else:
+        B, a, zz = O.quantize_greedy(W, q, g, mean_offset=(mode == L.LUTGEMM_Q_GREEDY_MEAN_OFFSET))
+    np.testing.assert_array_equal(bits, O.encode_bits(B))
+    np.testing.assert_array_equal(alpha.view(np.uint16), O.encode_alpha(a).view(np.uint16))
+    if zz is None:
+        assert z is None
+    else:
+        np.testing.assert_array_equal(z.view(np.uint16), O.encode_z(zz).view(np.uint16))
+    np.testing.assert_array_equal(L.lutgemm_unpack_bcq(bits, m, n, q), B)
+    np.testing.assert_array_equal(L.lutgemm_pack_planes(B), bits)
+    ap, zp = L.lutgemm_pack_scales(a, zz, n, g)
+    np.testing.assert_array_equal(ap.view(np.uint16), alpha.view(np.uint16))
+    if zz is not None:
+        np.testing.assert_array_equal(zp.view(np.uint16), z.view(np.uint16))
+
+
+def test_pack_planes_matches_hand_written_bytes(golden_dir):
+    cases, _ = _load_layout_cases(golden_dir)
+    for case in cases:
+        B = layout_case_planes(case)
+        packed = L.lutgemm_pack_planes(B)
+        want = np.zeros(case["size"], dtype=np.uint8)
+        for off, val in case["bytes"].items():
+            want[off] = val
+        np.testing.assert_array_equal(packed, want)
+
+
+def test_fp16_rounding_of_scales_is_single_and_to_nearest_even():
+    # group of 8 whose mean |w| falls exactly halfway between two fp16 values: ties to even.
+    # |w| = 7 x 1.0 and 1 x (1 + 2^-7): mean = 1 + 2^-10 exactly = the fp16 spacing at 1.0 (2^-10) -> representable
+    # use 1 + 2^-8 instead: mean = 1 + 2^-11, halfway between 1 and 1 + 2^-10 -> rounds to 1.0 (even)
+    W = np.ones((1, 8), dtype=np.float16)
+    W[0, 0] = np.float16(1 + 2.0 ** -8)
+    _, alpha, _ = L.lutgemm_pack_bcq(W, 1, 8)
+    assert float(alpha[0]) == 1.0
+    W[0, 1] = np.float16(1 + 2.0 ** -7)          # mean = 1 + 3 * 2^-11: halfway, rounds up to even 1 + 2^-9
+    _, alpha, _ = L.lutgemm_pack_bcq(W, 1, 8)
+    assert float(alpha[0]) == 1 + 2.0 ** -9
+    Bo, ao, _ = O.quantize_greedy(W, 1, 8)
+    assert ao[0, 0, 0] == alpha[0]
+
+
+def test_argument_validation_returns_codes_without_gpu():
+    lib = L.lib()
+    buf = np.zeros(64, dtype=np.uint8)
+    p = buf.ctypes.data
+    p16 = (p + 15) & ~15
+    # host entry points
+    assert lib.lutgemm_pack_bcq(None, 16, 64, 3, 64, 8, 0, p, p, None) == L.LUTGEMM_EINVAL
+    assert lib.lutgemm_pack_bcq(p, 16, 60, 3, 0, 8, 0, p, p, None) == L.LUTGEMM_EINVAL
+    assert lib.lutgemm_pack_bcq(p, 16, 64, 3, 64, 4, 0, p, p, None) == L.LUTGEMM_EUNSUPPORTED
+    assert lib.lutgemm_pack_bcq(p, 16, 64, 3, 64, 8, 7, p, p, None) == L.LUTGEMM_EUNSUPPORTED
+    assert lib.lutgemm_pack_bcq(p, 16, 64, 3, 64, 8, 1, p, p, None) == L.LUTGEMM_EINVAL      # offset mode needs z
+    # device entry points reject before any HIP call
+    args = dict(q=3, g=64, mu=8, m=16, n=64, flags=0)
+
+    def gemv(x=p16, bits=p16, alpha=p16, z=None, y=p16, ws=p16, wsb=1 << 20, **kw):
+        a = {**args, **kw}
+        return lib.lutgemm_gemv(x, bits, alpha, z, y, a["q"], a["g"], a["mu"], a["m"], a["n"], a["flags"], ws, wsb, None)
+
+    assert gemv(x=None) == L.LUTGEMM_EINVAL
+    assert gemv(y=None) == L.LUTGEMM_EINVAL
+    assert gemv(bits=p16 + 4) == L.LUTGEMM_EINVAL           # misaligned
+    assert gemv(n=60) == L.LUTGEMM_EINVAL
+    assert gemv(g=48) == L.LUTGEMM_EINVAL                    # n % g
+    assert gemv(g=12, n=96) == L.LUTGEMM_EINVAL              # g % 8
+    assert gemv(q=0) == L.LUTGEMM_EINVAL and gemv(q=9) == L.LUTGEMM_EINVAL
+    assert gemv(mu=4) == L.LUTGEMM_EUNSUPPORTED
+    assert gemv(flags=2) == L.LUTGEMM_EUNSUPPORTED
+    assert gemv(wsb=16) == L.LUTGEMM_EWORKSPACE
+    assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 33, 0, p16, 1 << 20, None) == L.LUTGEMM_EUNSUPPORTED
+    assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 0, 0, p16, 1 << 20, None) == L.LUTGEMM_EINVAL
+    assert lib.lutgemm_strerror(L.LUTGEMM_EWORKSPACE) == b"workspace too small"

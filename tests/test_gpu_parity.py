@@ -1,0 +1,134 @@
+"""GPU parity: lutgemm_gemv / lutgemm_gemm through the C ABI against the fp64 oracle,
+element by element, on seeded inputs spanning several tiles, ragged tails and the
+degenerate cases of the format."""
+import numpy as np
+import pytest
+
+import paper_2206_09557_amd as L
+from oracle import bcq_oracle as O
+from oracle import c_oracle
+from paper_2206_09557_amd import synth
+
+from gpu_util import Packed, check_parity, row_l1_bound, run
+
+pytestmark = pytest.mark.gpu
+
+MODES = {"greedy": L.LUTGEMM_Q_GREEDY, "greedy_z": L.LUTGEMM_Q_GREEDY_MEAN_OFFSET, "rtn": L.LUTGEMM_Q_UNIFORM_RTN}
+
+
+def _oracle_full(p, x16):
+    """fp64 y from the packed host buffers, numpy oracle (own decoder + definition)."""
+    return O.gemv_packed(p.bits, p.alpha, p.z, x16, p.m, p.n, p.q, p.g)
+
+
+def _bound(p):
+    g = p.n if p.g == 0 else p.g
+    NG = p.n // g
+    a = O.decode_alpha(p.alpha, p.m, NG, p.q)
+    z = None if p.z is None else O.decode_z(p.z, p.m, NG)
+    return row_l1_bound(a, z, g)
+
+
+# m, n, q, g, mode -- config 1 of the workload list first, then ragged / degenerate shapes
+CASES = [
+    (1024, 1024, 3, 128, "greedy"),      # single GEMV m = n = 1024, q = 3, g = 128, no offset
+    (50, 1544, 2, 8, "greedy_z"),        # ragged rows, last tile with 65 chunks, g = 8 (pair spans two groups)
+    (1000, 1536, 4, 128, "greedy_z"),    # last tile with exactly 64 chunks (one sub-slab)
+    (77, 520, 3, 0, "greedy"),           # single ragged tile, row-wise scales
+    (300, 2048, 3, 32, "rtn"),           # uniform -> BCQ with offset, small groups
+    (300, 2048, 2, 64, "rtn"),
+    (1, 8, 1, 8, "greedy"),              # smallest legal problem
+    (16, 8, 8, 8, "rtn"),
+    (4100, 3072, 3, 128, "greedy"),      # several workgroups per tile, ragged split of row blocks
+    (515, 5120, 4, 128, "greedy"),
+    (130, 1032, 5, 24, "greedy_z"),      # g % 16 != 0, second tile holds one chunk
+    (96, 1048, 3, 8, "rtn"),             # ragged tile AND split groups
+]
+
+
+@pytest.mark.parametrize("m,n,q,g,mode", CASES)
+def test_gemv_matches_oracle(m, n, q, g, mode):
+    print(f"case m={m} n={n} q={q} g={g} mode={mode}", flush=True)
+    W = synth.weights_fp16(m, n, seed=1000 + m + 7 * n + q)
+    x = synth.activations_fp16(n, seed=1500 + m + n)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    y_ref = _oracle_full(p, x)
+    bound = _bound(p)
+    y16 = run(p, x)
+    check_parity(y16, y_ref, x, bound)
+    y32 = run(p, x, f32_out=True)
+    check_parity(y32, y_ref, x, bound, f32_out=True)
+    # fp16 output is the single rounding of the fp32 result
+    np.testing.assert_array_equal(y32.astype(np.float16), y16)
+    # bitwise reproducible
+    np.testing.assert_array_equal(run(p, x, f32_out=True), y32)
+
+
+@pytest.mark.parametrize("q", range(1, 9))
+def test_every_q(q):
+    print(f"case q={q}", flush=True)
+    m, n, g = 200, 2560, 128
+    W = synth.weights_fp16(m, n, seed=2000 + q)
+    x = synth.activations_fp16(n, seed=2500 + q)
+    for mode in ("greedy", "rtn"):
+        p = Packed.from_weights(W, q, g, MODES[mode])
+        check_parity(run(p, x, f32_out=True), _oracle_full(p, x), x, _bound(p), f32_out=True)
+
+
+@pytest.mark.parametrize("batch", [1, 2, 5, 32])
+def test_gemm_batches(batch):
+    print(f"case batch={batch}", flush=True)
+    m, n, q, g = 333, 2048, 3, 128
+    W = synth.weights_fp16(m, n, seed=3000)
+    X = synth.activations_fp16(n, seed=3500 + batch, batch=batch)
+    for mode in ("greedy", "greedy_z"):
+        p = Packed.from_weights(W, q, g, MODES[mode])
+        Y = run(p, X, f32_out=True)
+        assert Y.shape == (batch, m)
+        bound = _bound(p)
+        for b in range(batch):
+            check_parity(Y[b], _oracle_full(p, X[b]), X[b], bound, f32_out=True)
+        Y16 = run(p, X)
+        np.testing.assert_array_equal(Y.astype(np.float16), Y16)
+
+
+def test_known_planes_unit_scale_signed_sum():
+    # q = 1, alpha = 1, z = 0: y_r = sum_k +-x_k, planes given directly (no quantiser)
+    rng = np.random.default_rng(4000)
+    m, n = 70, 1032
+    B = rng.choice(np.array([-1, 1], dtype=np.int8), size=(1, m, n))
+    B[0, 0, :] = 1
+    B[0, 1, :] = -1
+    bits = L.lutgemm_pack_planes(B)
+    ap, _ = L.lutgemm_pack_scales(np.ones((1, m, 1), dtype=np.float16), None, n, 0)
+    x = synth.activations_fp16(n, seed=4001)
+    p = Packed(bits, ap, None, m, n, 1, 0)
+    y = run(p, x, f32_out=True)
+    want = B[0].astype(np.float64) @ x.astype(np.float64)
+    np.testing.assert_allclose(y, want, rtol=0, atol=2e-4)
+    assert abs(y[0] + y[1]) < 1e-6
+
+
+def test_special_values_in_x():
+    # zeros, the largest finite fp16 scaled so that sums stay finite, subnormals
+    m, n, q, g = 64, 1024, 2, 128
+    W = synth.weights_fp16(m, n, seed=4100)
+    p = Packed.from_weights(W, q, g)
+    x = np.zeros(n, dtype=np.float16)
+    assert np.all(run(p, x, f32_out=True) == 0)
+    x = synth.activations_fp16(n, seed=4101)
+    x[::3] = 0
+    x[1::97] = np.float16(6.0e-8)       # subnormal
+    x[5::101] = np.float16(2048.0)
+    check_parity(run(p, x, f32_out=True), _oracle_full(p, x), x, _bound(p), f32_out=True)
+
+
+def test_runs_on_a_side_stream():
+    torch = pytest.importorskip("torch")
+    m, n, q, g = 512, 2048, 3, 128
+    W = synth.weights_fp16(m, n, seed=4200)
+    x = synth.activations_fp16(n, seed=4201)
+    p = Packed.from_weights(W, q, g)
+    s = torch.cuda.Stream()
+    y_side = run(p, x, f32_out=True, stream=s)
+    np.testing.assert_array_equal(y_side, run(p, x, f32_out=True))
