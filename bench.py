@@ -87,6 +87,7 @@ def main():
             "y": torch.empty(m, dtype=torch.float16, device="cuda"),
             "ws": torch.empty(wsb, dtype=torch.uint8, device="cuda"), "wsb": wsb,
         }
+        L.lutgemm_workspace_init(ent["ws"], wsb, torch.cuda.current_stream().cuda_stream)
         layers.append(ent)
         print(f"[bench] {name} {m}x{n} packed and uploaded ({time.time() - t_setup:.1f}s)", file=sys.stderr, flush=True)
 

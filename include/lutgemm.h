@@ -35,15 +35,23 @@
  * (only the last tile can have C < 128).  Slot (t, L), t < T, L < 64, of tile kt
  * stands for chunk 128*kt + T*L + t.
  *
- *   bits   one byte per (plane, row, chunk):
- *            offset = kt * RB * q * 2048
- *                   + ((rb * q + i) * T + t) * 1024 + L * 16 + rho
- *          Bytes of rows >= m and of slots whose chunk >= n/8 are 0.
+ *   bits   one byte per (plane, row, chunk), in slabs of 1024 bytes = 64 lanes x 16 bytes
+ *          per (tile, row block, plane, sub-slab):
+ *            slab offset = kt * RB * q * 2048 + ((rb * q + i) * T + t) * 1024
+ *          Inside a slab the four lanes of a quad hold four rows each, and the four
+ *          slots of the quad are rotated across them: with k = rho / 4 and the slot
+ *          written L = 4*j + c (quad j, c < 4), the key sits in
+ *            lane 4*j + k,  byte 4 * ((c - k) mod 4) + rho % 4,
+ *          i.e. at  slab offset + (4*j + k) * 16 + 4 * ((c - k) mod 4) + rho % 4.
+ *          (A lane thus owns rows 4k..4k+3; in its dword s it finds the keys of slot
+ *          4*j + (s + k) mod 4, so the four lanes of a quad always address four
+ *          different tables.)  Bytes of rows >= m and of slots whose chunk >= n/8 are 0.
  *          Size = RB * q * 1024 * (2 * (NT - 1) + T_last) bytes, which equals
  *          m*n*q/8 (the binary-weight term of section 3.4 eq. 4) when m % 16 == 0
  *          and n % 512 == 0.
- *   alpha  fp16, one per (plane, row, group), NG = n / g groups:
- *            index = ((rb * NG + G) * q + i) * 16 + rho
+ *   alpha  fp16, one per (plane, row, group), NG = n / g groups; the 16 rows of a block
+ *          are kept as four quarters of four rows, the planes of a quarter together:
+ *            index = (((rb * NG + G) * 4 + rho / 4) * q + i) * 4 + rho % 4
  *          Rows >= m hold 0.  Size = RB * NG * q * 32 bytes ( = 2*m*(n/g)*q, the
  *          scale term of eq. 4, when m % 16 == 0).
  *   z      fp16, one per (row, group):  index = (rb * NG + G) * 16 + rho.
@@ -98,9 +106,17 @@ size_t lutgemm_bits_bytes(int64_t m, int64_t n, int q);
 size_t lutgemm_alpha_bytes(int64_t m, int64_t n, int q, int g);
 size_t lutgemm_z_bytes(int64_t m, int64_t n, int g);
 
-/* Device scratch a gemv/gemm call needs (split-K partial sums: the per-tile partial
-   outputs that appendix B accumulates across thread blocks).  0 on invalid arguments.  */
+/* Device scratch a gemv/gemm call needs: 32 KB of arrival counters followed by the
+   split-K partial sums (the per-block partial outputs that appendix B accumulates
+   across thread blocks).  0 on invalid arguments.                                       */
 size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch);
+
+/* DEVICE.  Enqueue the one-time preparation of a freshly allocated workspace (zeroes its
+   arrival counters with a small kernel, so the call may be captured in a HIP graph).
+   Needed once per workspace, before the first gemv/gemm that uses it; every gemv/gemm
+   leaves the counters zero again when its kernel has finished.  A workspace whose first
+   32 KB the caller has zero-filled by other means needs no call.                        */
+int lutgemm_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* HOST.  Quantise W (fp16, row-major m x n, host memory) to q planes with group size g
    using `mode`, and write the packed layouts into host buffers of the sizes above.
@@ -127,11 +143,13 @@ int lutgemm_pack_scales(const uint16_t* alpha, const uint16_t* z, int64_t m, int
    (section 3.2: y = sum_i A_i o (B_i . x); offset term from eq. 3).
      x      fp16 [n]                       bits, alpha, z   packed layouts above (z nullable)
      y      fp16 [m] or fp32 [m] (flags); overwritten, never read
-     workspace  at least lutgemm_workspace_bytes(m, n, q, g, mu, 1) bytes; contents
-                need not be initialised and are undefined afterwards
+     workspace  at least lutgemm_workspace_bytes(m, n, q, g, mu, 1) bytes, prepared once
+                by lutgemm_workspace_init; beyond the first 32 KB its contents need not be
+                initialised and are undefined afterwards.  One workspace serves calls of
+                any shape it is large enough for
      hip_stream a hipStream_t (NULL = the null stream); the work is enqueued and the call
                 returns without waiting.  Calls that share a workspace must be ordered on
-                one stream.
+                one stream (two calls running at once need two workspaces).
    The result is bitwise reproducible from run to run.                                   */
 int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void* z, void* y,
                  int q, int g, int mu, int64_t m, int64_t n, unsigned flags,

@@ -219,7 +219,10 @@ def _bit_offset(m, n, q, i, r, c):
     C = min(128, n // 8 - 128 * kt)
     T = 2 if C > 64 else 1
     L, t = divmod(c - 128 * kt, T)
-    return kt * RB * q * 2048 + ((rb * q + i) * T + t) * 1024 + L * 16 + rho
+    j, cq = divmod(L, 4)           # quad and slot within the quad
+    k = rho // 4                   # the lane of the quad that owns this row
+    slab = kt * RB * q * 2048 + ((rb * q + i) * T + t) * 1024
+    return slab + (4 * j + k) * 16 + 4 * ((cq - k) % 4) + rho % 4
 
 
 def encode_bits(B):
@@ -249,9 +252,11 @@ def decode_bits(packed, m, n, q):
     T = np.where(C > 64, 2, 1)
     L = (c - 128 * kt) // T
     t = (c - 128 * kt) % T
+    j, cq, k = L // 4, L % 4, rho // 4
     B = np.empty((q, m, n), dtype=np.int8)
     for i in range(q):
-        off = kt * RB * q * 2048 + ((rb * q + i) * T + t) * 1024 + L * 16 + rho
+        off = (kt * RB * q * 2048 + ((rb * q + i) * T + t) * 1024
+               + (4 * j + k) * 16 + 4 * ((cq - k) % 4) + rho % 4)
         keys = packed[off]  # [m][n//8]
         bits = (keys[:, :, None] >> np.arange(8, dtype=np.uint8)) & 1
         B[i] = (2 * bits.astype(np.int8) - 1).reshape(m, n)
@@ -267,7 +272,7 @@ def encode_alpha(alpha):
     for i in range(q):
         for r in range(m):
             for G in range(NG):
-                out[(((r // 16) * NG + G) * q + i) * 16 + r % 16] = alpha[i, r, G]
+                out[((((r // 16) * NG + G) * 4 + (r % 16) // 4) * q + i) * 4 + r % 4] = alpha[i, r, G]
     return out
 
 
@@ -275,8 +280,8 @@ def decode_alpha(packed, m, NG, q):
     packed = np.asarray(packed).view(np.float16).ravel()
     RB = -(-m // 16)
     assert packed.size == RB * NG * q * 16
-    a = packed.reshape(RB, NG, q, 16)            # [rb][G][i][rho]
-    return np.ascontiguousarray(a.transpose(2, 0, 3, 1).reshape(q, RB * 16, NG)[:, :m, :])
+    a = packed.reshape(RB, NG, 4, q, 4)          # [rb][G][rho / 4][i][rho % 4]
+    return np.ascontiguousarray(a.transpose(3, 0, 2, 4, 1).reshape(q, RB * 16, NG)[:, :m, :])
 
 
 def encode_z(z):

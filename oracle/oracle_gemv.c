@@ -44,7 +44,9 @@ static int64_t key_offset(int64_t m, int64_t n, int q, int i, int64_t r, int64_t
   if (C > 128) C = 128;
   int64_t T = C > 64 ? 2 : 1;
   int64_t L = (c - 128 * kt) / T, t = (c - 128 * kt) % T;
-  return kt * RB * q * 2048 + ((rb * q + i) * T + t) * 1024 + L * 16 + rho;
+  int64_t j = L / 4, cq = L % 4, k = rho / 4; /* quad, slot in quad, owning lane of the quad */
+  int64_t slab = kt * RB * q * 2048 + ((rb * q + i) * T + t) * 1024;
+  return slab + (4 * j + k) * 16 + 4 * ((cq - k + 4) % 4) + rho % 4;
 }
 
 /*
@@ -80,7 +82,7 @@ int oracle_gemv_packed(const uint8_t* bits, const uint16_t* alpha, const uint16_
       for (int i = 0; i < q; ++i) {
         uint8_t key = bits[key_offset(m, n, q, i, r, k / 8)];
         double bsign = ((key >> (k % 8)) & 1) ? 1.0 : -1.0;
-        w += half_to_double(alpha[((rb * NG + G) * q + i) * 16 + rho]) * bsign;
+        w += half_to_double(alpha[(((rb * NG + G) * 4 + rho / 4) * q + i) * 4 + rho % 4]) * bsign;
       }
       if (z) w += half_to_double(z[(rb * NG + G) * 16 + rho]);
       for (int b = 0; b < batch; ++b) acc[b] += w * half_to_double(x[(int64_t)b * n + k]);

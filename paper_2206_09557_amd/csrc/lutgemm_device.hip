@@ -3,26 +3,34 @@
 // (paper section 3.1, section 3.2, appendix B), behind lutgemm_gemv / lutgemm_gemm.
 //
 // Mapping (this library's own; the paper's thread-block design was made for another GPU):
-//   * One workgroup of 16 wavefronts owns one K tile (1024 input columns = 128 tables
+//   * One workgroup of 8 wavefronts owns one K tile (1024 input columns = 128 tables
 //     of 256 fp32 entries = 128 KB of LDS) for a contiguous range of row blocks, so a
 //     table set is built once per workgroup and reused for thousands of rows.
-//   * Table (t, L) lives at LDS byte address  t<<16 | key<<8 | L<<2 : every lane of a
-//     wavefront reads its own table, whose 256 entries all sit in bank L, so a lookup
-//     wave is bank-conflict free for any keys, and the address is one byte permute of
-//     the packed key word.
-//   * A lane therefore accumulates, for 16 rows, the contribution of its own 16 input
-//     columns, already multiplied by the group's scales; a 64-lane transpose-reduce with
-//     DPP row operations turns 16 per-lane sums into 16 row sums.
-//   * The per-tile partial sums go to a workspace and a second small kernel adds the
-//     tiles in a fixed order (deterministic, unlike the atomic accumulation of appendix B).
+//   * Table (t, L) lives at LDS byte address  t<<16 | key<<8 | L<<2 : its 256 entries all
+//     sit in bank L, and the address of a lookup is one byte permute of the packed key word.
+//   * Inside a quad of lanes the rows are dealt out (lane k owns rows 4k..4k+3 of the
+//     16-row block) and the quad's four tables are visited in rotation (in its dword s lane
+//     k finds the keys of table 4j + (s+k) mod 4).  At any instant the 64 lanes address 64
+//     different tables, so a lookup wave is bank-conflict free for any keys, and a lane
+//     ends up with just four row sums whose scales are its own: no scale is fetched twice
+//     inside a quad, and the cross-lane reduction shrinks to four values over 16 quads.
+//   * The per-K-group partial sums go to a workspace; the last workgroup to finish a row
+//     range (an arrival counter per range) adds the groups in a fixed order and writes y,
+//     so the result does not depend on arrival order (unlike the atomic accumulation of
+//     appendix B) and no second kernel is needed.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
 
 #include "lutgemm.h"
 
 namespace {
 
-constexpr int kWaves = 16;
+#ifndef LUT_WAVES
+#define LUT_WAVES 8      // wavefronts per workgroup (two per SIMD: 256 registers each, no spilling)
+#endif
+constexpr int kWaves = LUT_WAVES;
 constexpr int kThreads = kWaves * 64;
 constexpr int kLutBytes = 2 * 256 * 64 * 4;  // two sub-slabs x 256 keys x 64 lanes x fp32
 
@@ -33,14 +41,20 @@ struct GemvParams {
   const uint8_t* bits;    // packed
   const __half* alpha;    // packed
   const __half* z;        // packed or null
-  float* partial;         // [NT][m_pad]
-  int64_t m_pad;
+  float* partial;         // this activation vector's partials: [KG][kg_stride]
+  uint32_t* counters;     // this activation vector's arrival counters: [row_splits]
+  void* y;                // this activation vector's output, fp16 or fp32 [m]
+  int64_t kg_stride;      // floats between the partials of consecutive K groups
+  int m;                  // rows
   int RB;                 // row blocks
   int NT;                 // K tiles
   int NG;                 // groups per row
   int g;                  // group size (columns)
   int nchunks;            // n / 8
-  int row_splits;         // workgroups per K tile
+  int KG;                 // K groups (workgroups along K)
+  int TPG;                // K tiles per K group
+  int row_splits;         // workgroups along the rows
+  int y_f32;              // output type
 };
 
 // DPP controls (GFX9 encoding)
@@ -59,6 +73,18 @@ __device__ __forceinline__ float lds_f32(uint32_t byte_addr) {
   return *(const __attribute__((address_space(3))) float*)(uintptr_t)byte_addr;
 }
 
+// The split-K partials cross workgroups (and L2s) inside one kernel.  They are written and
+// read with device-scope relaxed atomics only: such a store is written through to memory
+// and is complete once the wave's store counter has drained, and such a load does not hit
+// a stale cached copy.  A full device-scope fence would also work but writes back and
+// invalidates a whole L2 each time, which costs several microseconds per kernel.
+__device__ __forceinline__ void store_device_coherent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device_coherent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ float half_lo(uint32_t packed) {
   return __half2float(__ushort_as_half((unsigned short)(packed & 0xffffu)));
 }
@@ -73,59 +99,183 @@ __device__ __forceinline__ void build_tables(float* lut, int t, int kh, int lane
   float base = -(xs[0] + xs[1] + xs[2] + xs[3] + xs[4]);
 #pragma unroll
   for (int j = 5; j < 8; ++j) base += ((kh >> (j - 5)) & 1) ? xs[j] : -xs[j];
-  float e[32];
-  e[0] = base;
+  // two batches of 16 entries (key bit 4 clear, then set) keep the register footprint small:
+  // the first units of the row loop are already in flight while the tables are built
 #pragma unroll
-  for (int j = 0; j < 5; ++j) {
-    const float two_x = 2.0f * xs[j];
+  for (int hi = 0; hi < 2; ++hi) {
+    float e[16];
+    e[0] = hi ? base + 2.0f * xs[4] : base;
 #pragma unroll
-    for (int k = 0; k < (1 << j); ++k) e[k + (1 << j)] = e[k] + two_x;
+    for (int j = 0; j < 4; ++j) {
+      const float two_x = 2.0f * xs[j];
+#pragma unroll
+      for (int k = 0; k < (1 << j); ++k) e[k + (1 << j)] = e[k] + two_x;
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) lut[(t << 14) | ((kh * 32 + hi * 16 + k) << 6) | lane] = e[k];
   }
-#pragma unroll
-  for (int k = 0; k < 32; ++k) lut[(t << 14) | ((kh * 32 + k) << 6) | lane] = e[k];
 }
 
-// 16 per-lane values -> lane (L % 16) of every row of 16 lanes holds the 64-lane sum of
-// value number L % 16.  Halving exchange: at each step a lane keeps the half of its
-// values selected by one bit of its id and receives that half from its partner.
-__device__ __forceinline__ float transpose_reduce16(const float (&acc)[16], int lane) {
-  const bool b3 = lane & 8, b2 = lane & 4, b1 = lane & 2, b0 = lane & 1;
-  float s8[8], s4[4], s2[2];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const float keep = b3 ? acc[8 + i] : acc[i];
-    const float send = b3 ? acc[i] : acc[8 + i];
-    s8[i] = keep + dpp_f32<kDppRowMirror>(send);
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float keep = b2 ? s8[4 + i] : s8[i];
-    const float send = b2 ? s8[i] : s8[4 + i];
-    s4[i] = keep + dpp_f32<kDppRowHalfMirror>(send);
-  }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const float keep = b1 ? s4[2 + i] : s4[i];
-    const float send = b1 ? s4[i] : s4[2 + i];
-    s2[i] = keep + dpp_f32<kDppQuadSwap2>(send);
-  }
-  const float keep = b0 ? s2[1] : s2[0];
-  const float send = b0 ? s2[0] : s2[1];
-  float s = keep + dpp_f32<kDppQuadSwap1>(send);
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kDppRowRor8 = 0x128;       // lane i <- lane (i + 8) mod 16 within a row of 16
+
+// Four per-lane values (rows 4k..4k+3 of the block, k = lane % 4) -> every lane holds the
+// 64-lane sum (over the 16 quads) of ONE of its rows, and returns which: row_in_block.
+// Halving exchange over lane bits 2 and 3, then a plain sum over lane bits 4 and 5.
+__device__ __forceinline__ float quad_rows_reduce(const float (&acc)[4], int lane, int* row_in_block) {
+  const bool b2 = lane & 4, b3 = lane & 8;
+  const float keep0 = b2 ? acc[2] : acc[0], send0 = b2 ? acc[0] : acc[2];
+  const float keep1 = b2 ? acc[3] : acc[1], send1 = b2 ? acc[1] : acc[3];
+  const float h0 = keep0 + __shfl_xor(send0, 4);
+  const float h1 = keep1 + __shfl_xor(send1, 4);
+  const float keep = b3 ? h1 : h0, send = b3 ? h0 : h1;
+  float s = keep + dpp_f32<kDppRowRor8>(send);
   s += __shfl_xor(s, 16);
   s += __shfl_xor(s, 32);
+  *row_in_block = 4 * (lane & 3) + (b2 ? 2 : 0) + (b3 ? 1 : 0);
   return s;
 }
 
-// One workgroup: K tile kt, row blocks [rb0, rb1).  T = sub-slabs of the tile (1 or 2).
-// SPLIT: the two chunks of a lane may lie in different groups (g % 16 != 0).
-template <int Q, int T, bool HAS_Z, bool SPLIT>
-__device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int kt, int rb0, int rb1) {
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
+// How a lane gets the scales of its four rows.
+//   kAlphaQuad     the four slots of the quad lie in one group (g % (32 * T) == 0): one
+//                  fetch of four rows x q planes serves all the lane's lookups.
+//   kAlphaPerSlot  one fetch per dword (slot); the two chunks of a slot share a group
+//                  (g % 16 == 0, or T == 1).
+//   kAlphaPerChunk one fetch per (dword, sub-slab): g % 16 != 0 with T == 2.
+enum { kAlphaQuad = 0, kAlphaPerSlot = 1, kAlphaPerChunk = 2 };
 
-  // ---- table build (section 3.1; appendix B: each block fills its tables first) ----
+// What one wavefront fetches for planes I0 .. I0+QP-1 of one (K tile, row block) unit of a
+// Q-plane layer.  (Layers of up to four planes are fetched whole; more planes go in two
+// halves so that a wavefront never needs more registers than it has.)
+template <int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
+struct Unit {
+  static constexpr int NS = (AMODE == kAlphaQuad) ? 1 : 4;                 // scale sets along the dwords
+  static constexpr int NC = (AMODE == kAlphaPerChunk) ? T : 1;             // ... and along the sub-slabs
+  u32x4 w[QP][T];           // key words: dword s = four rows of slot 4j + (s + k) mod 4
+  u32x2 al[NS][NC][QP];     // fp16 scales of the lane's four rows
+  u32x2 zz[NS][NC];         // fp16 offsets of the lane's four rows (used when I0 == 0)
+  float prev;               // partial sum of the earlier tiles of this K group (used when I0 == 0)
+};
+
+// Group index of every (dword, sub-slab) of this lane in tile kt.
+template <int T>
+__device__ __forceinline__ void lane_groups(const GemvParams& p, int kt, int lane, int chunks_in_tile, int (&grp)[4][T]) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int slot = (lane & ~3) | ((s + lane) & 3);
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      const int cc = min(T * slot + t, chunks_in_tile - 1);
+      grp[s][t] = ((128 * kt + cc) * 8) / p.g;
+    }
+  }
+}
+
+// All loads are unconditional (no branch between a fetch and the waits of the compute that
+// follows it), so that the wait counters let later fetches stay in flight.
+template <int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
+__device__ __forceinline__ void load_unit(Unit<Q, I0, QP, T, AMODE, HAS_Z>& u, const GemvParams& p, int64_t tile_base,
+                                          int rb, int lane, const int (&grp)[4][T], const float* partial, int out_row,
+                                          bool add_prev) {
+  using U = Unit<Q, I0, QP, T, AMODE, HAS_Z>;
+  const u32x4* bp = reinterpret_cast<const u32x4*>(p.bits + tile_base + (int64_t)rb * Q * T * 1024) + lane;
+#pragma unroll
+  for (int i = 0; i < QP; ++i)
+#pragma unroll
+    for (int t = 0; t < T; ++t) u.w[i][t] = __builtin_nontemporal_load(bp + ((I0 + i) * T + t) * 64);
+#pragma unroll
+  for (int s = 0; s < U::NS; ++s)
+#pragma unroll
+    for (int c = 0; c < U::NC; ++c) {
+      const int64_t blk = (int64_t)rb * p.NG + grp[s][c];
+      const u32x2* ap = reinterpret_cast<const u32x2*>(p.alpha + ((blk * 4 + (lane & 3)) * Q) * 4);
+#pragma unroll
+      for (int i = 0; i < QP; ++i) u.al[s][c][i] = ap[I0 + i];
+      if (HAS_Z && I0 == 0) u.zz[s][c] = *reinterpret_cast<const u32x2*>(p.z + blk * 16 + (lane & 3) * 4);
+    }
+  // first tile of the K group: nothing to add (the value read is never used)
+  if (I0 == 0) u.prev = add_prev ? load_device_coherent(partial + rb * 16 + out_row) : 0.0f;
+}
+
+__device__ __forceinline__ float half_of(const u32x2& v, int j) {   // j-th of the 4 halves
+  const uint32_t wrd = (j & 2) ? v.y : v.x;
+  return (j & 1) ? half_hi(wrd) : half_lo(wrd);
+}
+
+// Lookup / accumulate / scale for the planes of u (section 3.1: partial sums are retrieved
+// and added, then multiplied by the scale; section 3.2 rule 2: one scale per run of
+// lookups), plus the offset term with the first planes.  acc[rho]: row 4k + rho of the block.
+template <int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
+__device__ __forceinline__ void accumulate_unit(const Unit<Q, I0, QP, T, AMODE, HAS_Z>& u,
+                                                const uint32_t (&lane_base)[4], const float (&sum_x)[4][T],
+                                                float (&acc)[4]) {
+  using U = Unit<Q, I0, QP, T, AMODE, HAS_Z>;
+#pragma unroll
+  for (int i = 0; i < QP; ++i) {
+#pragma unroll
+    for (int rho = 0; rho < 4; ++rho) {
+      // address bytes {0, t, key byte rho, slot * 4}: byte 1 of lane_base is the constant 1
+      const uint32_t sel_t[2] = {0x0c0c0000u | ((4u + rho) << 8), 0x0c010000u | ((4u + rho) << 8)};
+      float run = 0.0f;        // lookups that share one scale
+      bool run_open = false;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+          const float v = lds_f32(__builtin_amdgcn_perm(u.w[i][t][s], lane_base[s], sel_t[t]));
+          run = run_open ? run + v : v;
+          run_open = true;
+          const bool close = (AMODE == kAlphaPerChunk) || (AMODE == kAlphaPerSlot && t == T - 1) ||
+                             (s == 3 && t == T - 1);
+          if (close) {
+            const int ss = (AMODE == kAlphaQuad) ? 0 : s, cc = (AMODE == kAlphaPerChunk) ? t : 0;
+            acc[rho] = fmaf(half_of(u.al[ss][cc][i], rho), run, acc[rho]);
+            run_open = false;
+          }
+        }
+      }
+    }
+  }
+  if (HAS_Z && I0 == 0) {   // offset term of eq. 3: z[r][G] * (sum of the activations of the columns it covers)
+#pragma unroll
+    for (int s = 0; s < U::NS; ++s)
+#pragma unroll
+      for (int c = 0; c < U::NC; ++c) {
+        float sx;
+        if (AMODE == kAlphaQuad) {
+          sx = 0.0f;
+#pragma unroll
+          for (int s2 = 0; s2 < 4; ++s2)
+#pragma unroll
+            for (int t = 0; t < T; ++t) sx += sum_x[s2][t];
+        } else if (AMODE == kAlphaPerSlot) {
+          sx = (T == 2) ? sum_x[s][0] + sum_x[s][T - 1] : sum_x[s][0];
+        } else {
+          sx = sum_x[s][c];
+        }
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho) acc[rho] = fmaf(half_of(u.zz[s][c], rho), sx, acc[rho]);
+      }
+  }
+}
+
+// Whole-unit compute for layers fetched in one piece.  Returns the 64-lane sum for the row
+// quad_rows_reduce assigns to this lane.
+template <int Q, int T, int AMODE, bool HAS_Z>
+__device__ __forceinline__ float compute_unit(const Unit<Q, 0, Q, T, AMODE, HAS_Z>& u, int lane,
+                                              const uint32_t (&lane_base)[4], const float (&sum_x)[4][T],
+                                              int* row_in_block) {
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  accumulate_unit(u, lane_base, sum_x, acc);
+  return quad_rows_reduce(acc, lane, row_in_block);
+}
+
+// Table build of one tile (section 3.1; appendix B: each block fills its tables first),
+// ending with the workgroup barrier that publishes the tables.
+template <int T>
+__device__ __forceinline__ void build_tile_tables(const GemvParams& p, float* lut, int kt, int chunks_in_tile, int wave,
+                                                  int lane) {
   for (int slot = wave; slot < T * 8; slot += kWaves) {
     const int t = slot >> 3, kh = slot & 7;
     const int cc = T * lane + t;
@@ -143,134 +293,246 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
     build_tables(lut, t, kh, lane, xs);
   }
   __syncthreads();
+}
 
-  // ---- per-lane constants ----
-  uint32_t lane_base[T];
-  int grp[T];
-  float sum_x[T];
+// Per-lane lookup constants: dword s of this lane looks into the table of slot
+// 4j + (s + k) mod 4.  lane_base byte 0: slot * 4; byte 1: the constant 1 (source of the
+// sub-slab address bit).  sum_x: entry 0xFF of each table = the sum of its 8 activations.
+template <int T, bool HAS_Z>
+__device__ __forceinline__ void lane_tables(int lane, uint32_t (&lane_base)[4], float (&sum_x)[4][T]) {
 #pragma unroll
-  for (int t = 0; t < T; ++t) {
-    lane_base[t] = ((uint32_t)t << 16) | ((uint32_t)lane << 2);
-    const int cc = min(T * lane + t, chunks_in_tile - 1);
-    grp[t] = ((128 * kt + cc) * 8) / p.g;
-    sum_x[t] = HAS_Z ? lds_f32(lane_base[t] | (0xffu << 8)) : 0.0f;   // entry 0xFF = +x0..+x7
-  }
-  const float sum_x_pair = (T == 2) ? sum_x[0] + sum_x[T - 1] : sum_x[0];
-
-  const int64_t tile_base = (int64_t)kt * p.RB * Q * 2048;
-  float* partial = p.partial + (int64_t)kt * p.m_pad;
-
-  // ---- lookup / accumulate over this workgroup's row blocks ----
-  for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
-    const u32x4* bp = reinterpret_cast<const u32x4*>(p.bits + tile_base + (int64_t)rb * Q * T * 1024) + lane;
-    u32x4 w[Q][T];
+  for (int s = 0; s < 4; ++s) {
+    const uint32_t slot = ((uint32_t)lane & ~3u) | ((uint32_t)(s + lane) & 3u);
+    lane_base[s] = (slot << 2) | 0x100u;
 #pragma unroll
-    for (int i = 0; i < Q; ++i)
-#pragma unroll
-      for (int t = 0; t < T; ++t) w[i][t] = __builtin_nontemporal_load(bp + (i * T + t) * 64);
-
-    float acc[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-
-    constexpr int NA = SPLIT ? T : 1;   // distinct scale groups per lane
-#pragma unroll
-    for (int a = 0; a < NA; ++a) {
-      const u32x4* ap = reinterpret_cast<const u32x4*>(p.alpha + ((int64_t)rb * p.NG + grp[a]) * Q * 16);
-      u32x4 al[Q][2];
-#pragma unroll
-      for (int i = 0; i < Q; ++i) {
-        al[i][0] = ap[i * 2];
-        al[i][1] = ap[i * 2 + 1];
-      }
-#pragma unroll
-      for (int i = 0; i < Q; ++i) {
-        const uint32_t aw[8] = {al[i][0].x, al[i][0].y, al[i][0].z, al[i][0].w,
-                                al[i][1].x, al[i][1].y, al[i][1].z, al[i][1].w};
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const uint32_t sel = 0x0c020000u | ((4u + (r & 3)) << 8);   // {0, base.b2, key, base.b0}
-          float v;
-          if (SPLIT) {
-            v = lds_f32(__builtin_amdgcn_perm(w[i][a][r >> 2], lane_base[a], sel));
-          } else {
-            v = lds_f32(__builtin_amdgcn_perm(w[i][0][r >> 2], lane_base[0], sel));
-            if (T == 2) v += lds_f32(__builtin_amdgcn_perm(w[i][T - 1][r >> 2], lane_base[T - 1], sel));
-          }
-          const float a_r = (r & 1) ? half_hi(aw[r >> 1]) : half_lo(aw[r >> 1]);
-          acc[r] = fmaf(a_r, v, acc[r]);   // scale applied once per (row, group, plane): section 3.2 rule 2
-        }
-      }
-      if (HAS_Z) {  // offset term of eq. 3: z[r][G] * sum of the lane's activations
-        const u32x4* zp = reinterpret_cast<const u32x4*>(p.z + ((int64_t)rb * p.NG + grp[a]) * 16);
-        const u32x4 z0 = zp[0], z1 = zp[1];
-        const uint32_t zw[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
-        const float sx = SPLIT ? sum_x[a] : sum_x_pair;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float z_r = (r & 1) ? half_hi(zw[r >> 1]) : half_lo(zw[r >> 1]);
-          acc[r] = fmaf(z_r, sx, acc[r]);
-        }
-      }
-    }
-
-    const float s = transpose_reduce16(acc, lane);
-    if (lane < 16) partial[rb * 16 + lane] = s;
+    for (int t = 0; t < T; ++t)
+      sum_x[s][t] = HAS_Z ? lds_f32(((uint32_t)t << 16) | (0xffu << 8) | (slot << 2)) : 0.0f;
   }
 }
 
-template <int Q, bool HAS_Z, bool SPLIT>
+// One workgroup, one K tile kt, row blocks [rb0, rb1).  T = sub-slabs of the tile (1 or 2).
+// AMODE: how the lanes get their scales (see above).
+// first_tile: the partials are written; otherwise they are added to those of the earlier
+// tiles of the K group (each (wave, row block) pair is always served by the same wave).
+template <int Q, int T, int AMODE, bool HAS_Z, int kDepth>
+__device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int kt, int rb0, int rb1, float* partial,
+                                          bool first_tile) {
+  using U = Unit<Q, 0, Q, T, AMODE, HAS_Z>;
+  int lane = threadIdx.x & 63;
+  // Everything derived from the lane id below belongs to this tile only: the empty asm
+  // stops the optimiser from hoisting it out of the tile loop, where the values of the
+  // two-sub-slab and the one-sub-slab paths would all be live at once (and spill).
+  asm volatile("" : "+v"(lane));
+  // wave-uniform by construction; saying so keeps row-block indices and base addresses in SGPRs
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
+  const int64_t tile_base = (int64_t)kt * p.RB * Q * 2048;
+
+  int grp[4][T];
+  lane_groups<T>(p, kt, lane, chunks_in_tile, grp);
+  // the row of the 16-row block whose sum this lane ends up with (see quad_rows_reduce)
+  const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
+
+  if constexpr (Q > 4) {
+    // ---- more than four planes: no fetch-ahead, each unit in two halves ----
+    constexpr int QA = (Q + 1) / 2;
+    build_tile_tables<T>(p, lut, kt, chunks_in_tile, wave, lane);
+    uint32_t lane_base[4];
+    float sum_x[4][T];
+    lane_tables<T, HAS_Z>(lane, lane_base, sum_x);
+    for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
+      float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      Unit<Q, 0, QA, T, AMODE, HAS_Z> ua;
+      load_unit(ua, p, tile_base, rb, lane, grp, partial, out_row, !first_tile);
+      accumulate_unit(ua, lane_base, sum_x, acc);
+      Unit<Q, QA, Q - QA, T, AMODE, HAS_Z> ub;
+      load_unit(ub, p, tile_base, rb, lane, grp, partial, out_row, !first_tile);
+      accumulate_unit(ub, lane_base, sum_x, acc);
+      int row_in_block;
+      const float s = quad_rows_reduce(acc, lane, &row_in_block) + ua.prev;
+      store_device_coherent(partial + rb * 16 + row_in_block, s);
+    }
+  } else {
+  // Units of this wavefront: rb0 + wave + j * kWaves.  kDepth units are fetched ahead of
+  // the one being computed; the first fetches are issued before the tables are built, so
+  // that the HBM latency overlaps the build.  Fetches past the wavefront's last unit are
+  // redirected to the range's last row block (a harmless re-read) instead of branching.
+  U u[kDepth + 1];
+  const int rb_first = rb0 + wave;
+  const int rb_clamp = rb1 - 1;
+#pragma unroll
+  for (int d = 0; d < kDepth; ++d)
+    load_unit(u[d], p, tile_base, min(rb_first + d * kWaves, rb_clamp), lane, grp, partial, out_row, !first_tile);
+
+  build_tile_tables<T>(p, lut, kt, chunks_in_tile, wave, lane);
+  uint32_t lane_base[4];
+  float sum_x[4][T];
+  lane_tables<T, HAS_Z>(lane, lane_base, sum_x);
+
+  // ---- lookup / accumulate over this workgroup's row blocks ----
+  // Four units per trip: the unit buffers rotate by name (kDepth + 1 divides 4), and the
+  // four results are parked in ONE register (unit j of the trip in lanes 16j..16j+15) and
+  // written by a single store after the fetches of the next trip have been issued.  A
+  // store shares the wave's memory counter with the loads, so an outstanding store issued
+  // BEFORE a load makes every wait for that load wait for the store's round trip as well;
+  // fewer stores, each younger than the loads in flight, keep that off the critical path.
+  static_assert(4 % (kDepth + 1) == 0, "the unit buffers must rotate with period 4");
+  const int lane_row = lane >> 4;
+  int rb = rb_first;
+  for (; rb + 3 * kWaves < rb1; rb += 4 * kWaves) {
+    float parked = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // kDepth == 0: the unit itself, fetched just in time
+      load_unit(u[(j + kDepth) % (kDepth + 1)], p, tile_base, min(rb + (j + kDepth) * kWaves, rb_clamp), lane, grp,
+                partial, out_row, !first_tile);
+      int row_in_block;
+      const float s = compute_unit(u[j % (kDepth + 1)], lane, lane_base, sum_x, &row_in_block) + u[j % (kDepth + 1)].prev;
+      parked = (lane_row == j) ? s : parked;
+    }
+    store_device_coherent(partial + (rb + lane_row * kWaves) * 16 + out_row, parked);
+  }
+  // the last one to three units of this wavefront
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int rb_cur = rb + j * kWaves;
+    if (rb_cur >= rb1) break;
+    load_unit(u[(j + kDepth) % (kDepth + 1)], p, tile_base, min(rb_cur + kDepth * kWaves, rb_clamp), lane, grp,
+              partial, out_row, !first_tile);
+    int row_in_block;
+    const float s = compute_unit(u[j % (kDepth + 1)], lane, lane_base, sum_x, &row_in_block) + u[j % (kDepth + 1)].prev;
+    // the four rows of 16 lanes hold, and store, the same 16 sums
+    store_device_coherent(partial + rb_cur * 16 + row_in_block, s);
+  }
+  }   // Q <= 4
+}
+
+// Units fetched ahead of the one being computed: one where two units fit the 256 registers
+// of a wavefront without spilling (any use of scratch memory costs far more than it hides).
+constexpr int prefetch_depth(int q, int amode) {
+#ifdef LUT_DEPTH
+  return LUT_DEPTH;
+#else
+  return (amode == kAlphaQuad && q <= 4) || (amode == kAlphaPerSlot && q <= 3) ? 1 : 0;   // q > 4: unused
+#endif
+}
+
+// AM2 / AM1: scale modes of the two-sub-slab tiles and of a one-sub-slab last tile.
+template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
   __shared__ float lut[kLutBytes / 4];
   // The lookup addresses are formed as if the tables start at LDS address 0.
   if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
-  const int kt = blockIdx.x % p.NT;
-  const int rs = blockIdx.x / p.NT;
+  const int kg = blockIdx.x % p.KG;
+  const int rs = blockIdx.x / p.KG;
   const int rb0 = (int)((int64_t)p.RB * rs / p.row_splits);
   const int rb1 = (int)((int64_t)p.RB * (rs + 1) / p.row_splits);
-  const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
-  if (chunks_in_tile > 64)
-    tile_body<Q, 2, HAS_Z, SPLIT>(p, lut, kt, rb0, rb1);
-  else
-    tile_body<Q, 1, HAS_Z, false>(p, lut, kt, rb0, rb1);
+  float* partial = p.partial + (int64_t)kg * p.kg_stride;
+
+  for (int ti = 0; ti < p.TPG; ++ti) {
+    const int kt = kg * p.TPG + ti;
+    if (kt >= p.NT) break;
+    if (ti > 0) __syncthreads();   // every lookup of the previous tile is done before its tables are overwritten
+    if (min(128, p.nchunks - 128 * kt) > 64)
+      tile_body<Q, 2, AM2, HAS_Z, prefetch_depth(Q, AM2)>(p, lut, kt, rb0, rb1, partial, ti == 0);
+    else
+      tile_body<Q, 1, AM1, HAS_Z, prefetch_depth(Q, AM1)>(p, lut, kt, rb0, rb1, partial, ti == 0);
+  }
+
+  // ---- cross-group reduction by the last workgroup to arrive for this row range ----
+  // (appendix B accumulates the per-block partial outputs with atomics; here the groups
+  // are added in index order by whoever arrives last, so y is reproducible bit for bit.)
+  __syncthreads();                 // every partial store has completed, every lookup is done: the table memory is free
+  uint32_t* flag = reinterpret_cast<uint32_t*>(lut);
+  if (threadIdx.x == 0) {
+    // Issued after the barrier, hence after the completion of every partial store of this
+    // workgroup (the barrier drains the store counters of all its wavefronts).
+    const uint32_t arrived = __hip_atomic_fetch_add(p.counters + rs, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    flag[0] = (arrived == (uint32_t)(p.KG - 1)) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (flag[0] == 0u) return;
+  // Four rows per thread per pass, 16 K groups per row per batch: 64 independent loads in
+  // flight per thread, because every one of them goes to memory (the partials were
+  // written through by other workgroups).  Addresses are clamped, not predicated; the sum
+  // over the groups of a row always runs in ascending group order.
+  constexpr int kRowsPerPass = 4;
+  const int row_end = min(rb1 * 16, p.m);
+  for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
+    const float* src[kRowsPerPass];
+    float sum[kRowsPerPass];
+#pragma unroll
+    for (int j = 0; j < kRowsPerPass; ++j) {
+      src[j] = p.partial + min(r0 + j * kThreads, row_end - 1);
+      sum[j] = 0.0f;
+    }
+    for (int kb = 0; kb < p.KG; kb += 16) {
+      float v[kRowsPerPass][16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
+#pragma unroll
+        for (int j = 0; j < kRowsPerPass; ++j) v[j][u] = load_device_coherent(src[j] + off);
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const bool live = kb + u < p.KG;
+#pragma unroll
+        for (int j = 0; j < kRowsPerPass; ++j) sum[j] += live ? v[j][u] : 0.0f;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kRowsPerPass; ++j) {
+      const int r = r0 + j * kThreads;
+      if (r < row_end) {
+        if (p.y_f32)
+          static_cast<float*>(p.y)[r] = sum[j];
+        else
+          static_cast<__half*>(p.y)[r] = __float2half_rn(sum[j]);   // fp16 output, nearest even (paper table 1)
+      }
+    }
+  }
+  if (threadIdx.x == 0)            // leave the counter at zero for the next call on this workspace
+    __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// y[b][r] = sum over K tiles of partial[(kt * batch + b)][r], in tile order (appendix B's
-// cross-block accumulation, made order-fixed), rounded to the output type.
-template <bool F32OUT>
-__global__ __launch_bounds__(256) void lutgemm_reduce_kernel(const float* __restrict__ partial, void* __restrict__ y,
-                                                             int64_t m, int64_t m_pad, int NT, int batch) {
-  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int b = blockIdx.y;
-  if (r >= m) return;
-  float s = 0.0f;
-  for (int kt = 0; kt < NT; ++kt) s += partial[((int64_t)kt * batch + b) * m_pad + r];
-  if (F32OUT)
-    static_cast<float*>(y)[(int64_t)b * m + r] = s;
-  else
-    static_cast<__half*>(y)[(int64_t)b * m + r] = __float2half_rn(s);
+// Zero the arrival counters of a fresh workspace.
+__global__ __launch_bounds__(256) void lutgemm_zero_counters_kernel(uint32_t* counters, int count) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < count) counters[i] = 0u;
 }
 
 using GemvKernel = void (*)(GemvParams);
 
-template <bool HAS_Z, bool SPLIT>
+template <bool HAS_Z, int AM2, int AM1>
 GemvKernel pick_q(int q) {
+#ifdef LUT_ONLY_Q   // development builds: one plane count only
+  return q == LUT_ONLY_Q ? lutgemm_gemv_kernel<LUT_ONLY_Q, HAS_Z, AM2, AM1> : nullptr;
+#else
   switch (q) {
-    case 1: return lutgemm_gemv_kernel<1, HAS_Z, SPLIT>;
-    case 2: return lutgemm_gemv_kernel<2, HAS_Z, SPLIT>;
-    case 3: return lutgemm_gemv_kernel<3, HAS_Z, SPLIT>;
-    case 4: return lutgemm_gemv_kernel<4, HAS_Z, SPLIT>;
-    case 5: return lutgemm_gemv_kernel<5, HAS_Z, SPLIT>;
-    case 6: return lutgemm_gemv_kernel<6, HAS_Z, SPLIT>;
-    case 7: return lutgemm_gemv_kernel<7, HAS_Z, SPLIT>;
-    case 8: return lutgemm_gemv_kernel<8, HAS_Z, SPLIT>;
+    case 1: return lutgemm_gemv_kernel<1, HAS_Z, AM2, AM1>;
+    case 2: return lutgemm_gemv_kernel<2, HAS_Z, AM2, AM1>;
+    case 3: return lutgemm_gemv_kernel<3, HAS_Z, AM2, AM1>;
+    case 4: return lutgemm_gemv_kernel<4, HAS_Z, AM2, AM1>;
+    case 5: return lutgemm_gemv_kernel<5, HAS_Z, AM2, AM1>;
+    case 6: return lutgemm_gemv_kernel<6, HAS_Z, AM2, AM1>;
+    case 7: return lutgemm_gemv_kernel<7, HAS_Z, AM2, AM1>;
+    case 8: return lutgemm_gemv_kernel<8, HAS_Z, AM2, AM1>;
   }
   return nullptr;
+#endif
 }
 
-GemvKernel pick_kernel(int q, bool has_z, bool split) {
-  if (has_z) return split ? pick_q<true, true>(q) : pick_q<true, false>(q);
-  return split ? pick_q<false, true>(q) : pick_q<false, false>(q);
+template <bool HAS_Z>
+GemvKernel pick_mode(int q, int64_t g) {
+  if (g % 64 == 0) return pick_q<HAS_Z, kAlphaQuad, kAlphaQuad>(q);
+  if (g % 32 == 0) return pick_q<HAS_Z, kAlphaPerSlot, kAlphaQuad>(q);
+  if (g % 16 == 0) return pick_q<HAS_Z, kAlphaPerSlot, kAlphaPerSlot>(q);
+  return pick_q<HAS_Z, kAlphaPerChunk, kAlphaPerSlot>(q);
+}
+
+GemvKernel pick_kernel(int q, bool has_z, int64_t g) {
+  return has_z ? pick_mode<true>(q, g) : pick_mode<false>(q, g);
 }
 
 int compute_units() {
@@ -287,9 +549,51 @@ int compute_units() {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+int env_int(const char* name) {
+  const char* v = getenv(name);
+  return v ? atoi(v) : 0;
+}
+
+// Workgroup grid: KG groups of TPG consecutive K tiles times row_splits row ranges, one
+// workgroup per compute unit.  Cost model in units of one (tile, row block) per wavefront:
+// the slowest wavefront's units plus a table build per tile, plus the cross-group sum.
+void choose_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
+  double best = 1e30;
+  const int max_rs = (RB + kWaves - 1) / kWaves;
+  for (int tpg = 1; tpg <= NT && tpg <= 8; ++tpg) {
+    const int kg = (NT + tpg - 1) / tpg;
+    int rs = cus / kg;
+    rs = rs < 1 ? 1 : (rs > max_rs ? max_rs : rs);
+    const int blocks = (RB + rs - 1) / rs;
+    const int rounds = (blocks + kWaves - 1) / kWaves;
+    const int tiles = (NT + kg - 1) / kg;
+    const double cost = tiles * (rounds + 0.5) + 0.03 * kg + 0.3 * (tpg - 1);
+    if (cost < best) {
+      best = cost;
+      *KG = kg;
+      *TPG = tpg;
+      *RS = rs;
+    }
+  }
+}
+
+constexpr size_t kCounterBytes = 32768;   // 32 activation vectors x 256 row ranges
+
 }  // namespace
 
 extern "C" {
+
+int lutgemm_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace || !aligned16(workspace)) return LUTGEMM_EINVAL;
+  if (workspace_bytes < kCounterBytes) return LUTGEMM_EWORKSPACE;
+  uint32_t* counters = static_cast<uint32_t*>(workspace);
+  int count = (int)(kCounterBytes / 4);
+  void* args[] = {&counters, &count};
+  if (hipLaunchKernel(reinterpret_cast<const void*>(lutgemm_zero_counters_kernel), dim3(count / 256), dim3(256), args,
+                      0, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return LUTGEMM_EHIP;
+  return LUTGEMM_OK;
+}
 
 int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void* z, void* y,
                  int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
@@ -314,43 +618,45 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.bits = static_cast<const uint8_t*>(bits);
   p.alpha = static_cast<const __half*>(alpha);
   p.z = static_cast<const __half*>(z);
+  p.m = (int)m;
   p.RB = (int)((m + 15) / 16);
-  p.m_pad = (int64_t)p.RB * 16;
   p.nchunks = (int)(n / 8);
   p.NT = (p.nchunks + 127) / 128;
   p.NG = (int)(n / gg);
   p.g = (int)gg;
-  // One workgroup per compute unit: split the rows of every K tile so that NT * splits
-  // fills the chip, but keep at least one row block per wavefront.
-  int splits = cus / p.NT;
-  splits = splits < 1 ? 1 : splits;
-  const int max_splits = (p.RB + kWaves - 1) / kWaves;
-  p.row_splits = splits > max_splits ? max_splits : splits;
+  p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
+  choose_grid(cus > 256 ? 256 : cus, p.NT, p.RB, &p.KG, &p.TPG, &p.row_splits);
+  {  // tuning overrides for sweeps
+    const int tpg = env_int("LUTGEMM_TPG"), rs = env_int("LUTGEMM_RS");
+    const int max_rs = (p.RB + kWaves - 1) / kWaves;
+    if (tpg > 0) {
+      p.TPG = tpg > p.NT ? p.NT : tpg;
+      p.KG = (p.NT + p.TPG - 1) / p.TPG;
+      p.row_splits = (cus > 256 ? 256 : cus) / p.KG;
+      p.row_splits = p.row_splits < 1 ? 1 : (p.row_splits > max_rs ? max_rs : p.row_splits);
+    }
+    if (rs > 0) p.row_splits = rs > 256 ? 256 : (rs > p.RB ? p.RB : rs);
+  }
+  const int64_t m_pad = (int64_t)p.RB * 16;
+  p.kg_stride = m_pad * batch;
 
-  const bool split_alpha = (gg % 16) != 0;
-  GemvKernel kern = pick_kernel(q, z != nullptr, split_alpha);
+  GemvKernel kern = pick_kernel(q, z != nullptr, gg);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
 
+  uint32_t* counters = static_cast<uint32_t*>(workspace);
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
   for (int b = 0; b < batch; ++b) {
-    // partial index: (kt * batch + b) * m_pad  ->  base b * m_pad, tile stride batch * m_pad
     GemvParams pb = p;
     pb.x = static_cast<const __half*>(x) + (int64_t)b * n;
-    pb.partial = static_cast<float*>(workspace) + (int64_t)b * p.m_pad;
-    pb.m_pad = p.m_pad * batch;
+    pb.partial = partials + (int64_t)b * m_pad;
+    pb.counters = counters + (int64_t)b * 256;
+    pb.y = p.y_f32 ? static_cast<void*>(static_cast<float*>(y) + (int64_t)b * m)
+                   : static_cast<void*>(static_cast<__half*>(y) + (int64_t)b * m);
     void* args[] = {&pb};
-    if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.NT * p.row_splits), dim3(kThreads), args, 0,
+    if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.KG * p.row_splits), dim3(kThreads), args, 0,
                         stream) != hipSuccess)
       return LUTGEMM_EHIP;
   }
-  const float* partial = static_cast<const float*>(workspace);
-  int64_t m_arg = m, m_pad_arg = p.m_pad;
-  int nt_arg = p.NT, batch_arg = batch;
-  void* rargs[] = {&partial, &y, &m_arg, &m_pad_arg, &nt_arg, &batch_arg};
-  const void* rkern = (flags & LUTGEMM_Y_F32) ? reinterpret_cast<const void*>(lutgemm_reduce_kernel<true>)
-                                              : reinterpret_cast<const void*>(lutgemm_reduce_kernel<false>);
-  if (hipLaunchKernel(rkern, dim3((unsigned)((m + 255) / 256), (unsigned)batch), dim3(256), rargs, 0, stream) !=
-      hipSuccess)
-    return LUTGEMM_EHIP;
   return LUTGEMM_OK;
 }
 

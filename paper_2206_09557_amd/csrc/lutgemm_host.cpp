@@ -41,9 +41,12 @@ inline int tile_T(const Shape& s, int64_t kt) {
   return C > 64 ? 2 : 1;
 }
 
-// Per-chunk part of the key offset: tile base + sub-slab + lane, and the tile's T.
+// Per-chunk part of the key offset: slab base of (tile, sub-slab), the quad and the slot
+// inside the quad, and the tile's T.
 struct ChunkSlot {
-  int64_t base;  // kt*RB*q*2048 + t*1024 + L*16
+  int64_t base;  // kt*RB*q*2048 + t*1024
+  int quad;      // j: lanes 4j..4j+3
+  int cq;        // slot within the quad
   int T;
 };
 
@@ -54,15 +57,20 @@ std::vector<ChunkSlot> chunk_slots(const Shape& s) {
     int T = tile_T(s, kt);
     int64_t cc = c - kt * kChunksPerTile;
     int64_t L = cc / T, t = cc % T;
-    v[c].base = kt * s.RB * s.q * 2 * kSlabBytes + t * kSlabBytes + L * 16;
+    v[c].base = kt * s.RB * s.q * 2 * kSlabBytes + t * kSlabBytes;
+    v[c].quad = (int)(L / 4);
+    v[c].cq = (int)(L % 4);
     v[c].T = T;
   }
   return v;
 }
 
+// The lane of the quad that owns row rho is k = rho / 4; it keeps the keys of slot cq in
+// its dword (cq - k) mod 4, byte rho % 4.
 inline int64_t key_offset(const Shape& s, const ChunkSlot& cs, int i, int64_t r) {
   int64_t rb = r / kRowsPerBlock, rho = r % kRowsPerBlock;
-  return cs.base + (rb * s.q + i) * cs.T * kSlabBytes + rho;
+  int64_t k = rho / 4;
+  return cs.base + (rb * s.q + i) * cs.T * kSlabBytes + (4 * cs.quad + k) * 16 + 4 * ((cs.cq - k + 4) % 4) + rho % 4;
 }
 
 size_t bits_bytes(const Shape& s) {
@@ -166,8 +174,8 @@ size_t lutgemm_z_bytes(int64_t m, int64_t n, int g) {
 size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch) {
   Shape s;
   if (mu != 8 || batch < 1 || batch > 32 || !make_shape(m, n, q, g, &s)) return 0;
-  // one fp32 partial per (K tile, activation vector, padded row)
-  return (size_t)s.NT * batch * s.RB * kRowsPerBlock * sizeof(float);
+  // arrival counters (32 KB), then one fp32 partial per (K tile, activation vector, padded row)
+  return (size_t)32768 + (size_t)s.NT * batch * s.RB * kRowsPerBlock * sizeof(float);
 }
 
 int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int mu, int mode,
@@ -196,7 +204,8 @@ int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int 
       for (int64_t gi = 0; gi < s.NG; ++gi) {
         const uint16_t* w = W + r * n + gi * G;
         for (int64_t k = 0; k < G; ++k) res[k] = half_to_float(w[k]);
-        uint16_t* a_dst = alpha_out + ((rb * s.NG + gi) * q) * kRowsPerBlock + rho;
+        // plane i of this (row, group) sits at a_dst[i * 4]: quarters of four rows, planes together
+        uint16_t* a_dst = alpha_out + (((rb * s.NG + gi) * 4 + rho / 4) * q) * 4 + rho % 4;
         uint16_t* z_dst = z_out ? z_out + (rb * s.NG + gi) * kRowsPerBlock + rho : nullptr;
 
         if (mode == LUTGEMM_Q_UNIFORM_RTN) {
@@ -221,7 +230,7 @@ int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int 
           float zsum = 0.0f;
           for (int i = 0; i < q; ++i) {
             const uint16_t a16 = double_to_half((double)(std::ldexp(1.0f, i - 1) * sf));
-            a_dst[i * kRowsPerBlock] = a16;
+            a_dst[i * 4] = a16;
             zsum = zsum + half_to_float(a16);
             for (int64_t c = 0; c < cpg; ++c) {
               unsigned key = 0;
@@ -241,7 +250,7 @@ int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int 
         }
         for (int i = 0; i < q; ++i) {
           const uint16_t a16 = double_to_half(seq_sum_abs(res.data(), G) / (double)G);
-          a_dst[i * kRowsPerBlock] = a16;
+          a_dst[i * 4] = a16;
           const float af = half_to_float(a16);
           for (int64_t c = 0; c < cpg; ++c) {
             unsigned key = 0;
@@ -314,7 +323,7 @@ int lutgemm_pack_scales(const uint16_t* alpha, const uint16_t* z, int64_t m, int
     const int64_t rb = r / kRowsPerBlock, rho = r % kRowsPerBlock;
     for (int64_t gi = 0; gi < s.NG; ++gi) {
       for (int i = 0; i < q; ++i)
-        alpha_out[((rb * s.NG + gi) * q + i) * kRowsPerBlock + rho] = alpha[((int64_t)i * m + r) * s.NG + gi];
+        alpha_out[(((rb * s.NG + gi) * 4 + rho / 4) * q + i) * 4 + rho % 4] = alpha[((int64_t)i * m + r) * s.NG + gi];
       if (z) z_out[(rb * s.NG + gi) * kRowsPerBlock + rho] = z[r * s.NG + gi];
     }
   }

@@ -28,6 +28,7 @@ _SIGNATURES = {
     "lutgemm_pack_planes": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int, _c.c_int, _c.c_void_p]),
     "lutgemm_pack_scales": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int, _c.c_int,
                                        _c.c_void_p, _c.c_void_p]),
+    "lutgemm_workspace_init": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "lutgemm_gemv": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                 _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_uint,
                                 _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -158,6 +159,10 @@ def lutgemm_pack_scales(alpha, z, n, g):
 
 
 # ---- device --------------------------------------------------------------------------
+def lutgemm_workspace_init(workspace, workspace_bytes, stream=0):
+    _check(lib().lutgemm_workspace_init(_addr(workspace), workspace_bytes, stream or None), "lutgemm_workspace_init")
+
+
 def lutgemm_gemv(x, bits, alpha, z, y, q, g, mu, m, n, flags, workspace, workspace_bytes, stream=0):
     _check(lib().lutgemm_gemv(_addr(x), _addr(bits), _addr(alpha), _addr(z), _addr(y), q, g, mu, m, n, flags,
                               _addr(workspace), workspace_bytes, stream or None), "lutgemm_gemv")

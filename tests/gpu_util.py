@@ -28,28 +28,41 @@ class Packed:
         return cls(bits, alpha, z, W.shape[0], W.shape[1], q, g)
 
 
-def run(packed, x16, f32_out=False, stream=None, poison=True):
-    """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x) for the packed layer."""
+def make_workspace(nbytes, stream=None):
+    """A workspace prepared as the header asks: garbage everywhere, then
+    lutgemm_workspace_init (which only has to zero the arrival counters)."""
+    torch = torch_cuda()
+    d_ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    d_ws.fill_(0xFF)
+    torch.cuda.synchronize()
+    s = torch.cuda.current_stream() if stream is None else stream
+    L.lutgemm_workspace_init(d_ws, nbytes, s.cuda_stream)
+    s.synchronize()
+    return d_ws
+
+
+def run(packed, x16, f32_out=False, stream=None, workspace=None):
+    """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x) for the packed layer.
+    y is pre-filled with NaN: it must be fully overwritten, never read."""
     torch = torch_cuda()
     p = packed
     x16 = np.ascontiguousarray(x16, dtype=np.float16)
     batch = 1 if x16.ndim == 1 else x16.shape[0]
     d_x = torch.from_numpy(x16.view(np.int16)).cuda()
     ydt = torch.float32 if f32_out else torch.float16
-    d_y = torch.empty((batch, p.m), dtype=ydt, device="cuda")
+    d_y = torch.full((batch, p.m), float("nan"), dtype=ydt, device="cuda")
     wsb = L.lutgemm_workspace_bytes(p.m, p.n, p.q, p.g, 8, batch)
-    d_ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
-    if poison:          # y and the workspace must be fully overwritten, never read
-        d_y.fill_(float("nan"))
-        d_ws.fill_(0xFF)
+    d_ws = make_workspace(wsb, stream) if workspace is None else workspace
+    assert d_ws.numel() >= wsb
     s = torch.cuda.current_stream() if stream is None else stream
     flags = L.LUTGEMM_Y_F32 if f32_out else L.LUTGEMM_Y_F16
     torch.cuda.synchronize()
     if x16.ndim == 1:
-        L.lutgemm_gemv(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, flags, d_ws, wsb, s.cuda_stream)
-    else:
-        L.lutgemm_gemm(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws, wsb,
+        L.lutgemm_gemv(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, flags, d_ws, d_ws.numel(),
                        s.cuda_stream)
+    else:
+        L.lutgemm_gemm(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
+                       d_ws.numel(), s.cuda_stream)
     s.synchronize()
     y = d_y.cpu().numpy()
     return y[0] if x16.ndim == 1 else y

@@ -46,7 +46,7 @@ def test_size_helpers_follow_eq4():
     assert L.lutgemm_alpha_bytes(16, 64, 3, 24) == 0 and L.lutgemm_alpha_bytes(16, 64, 3, 12) == 0
     assert L.lutgemm_workspace_bytes(16, 64, 3, 64, mu=4) == 0
     assert L.lutgemm_workspace_bytes(16, 64, 3, 64, batch=33) == 0
-    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128) == 12 * 49152 * 4
+    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128) == 32768 + 12 * 49152 * 4
 
 
 @pytest.mark.parametrize("m,n,q,g,mode", [
@@ -134,4 +134,6 @@ def test_argument_validation_returns_codes_without_gpu():
     assert gemv(wsb=16) == L.LUTGEMM_EWORKSPACE
     assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 33, 0, p16, 1 << 20, None) == L.LUTGEMM_EUNSUPPORTED
     assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 0, 0, p16, 1 << 20, None) == L.LUTGEMM_EINVAL
+    assert lib.lutgemm_workspace_init(None, 1 << 20, None) == L.LUTGEMM_EINVAL
+    assert lib.lutgemm_workspace_init(p16, 1024, None) == L.LUTGEMM_EWORKSPACE
     assert lib.lutgemm_strerror(L.LUTGEMM_EWORKSPACE) == b"workspace too small"

@@ -9,7 +9,7 @@ from oracle import bcq_oracle as O
 from oracle import c_oracle
 from paper_2206_09557_amd import synth
 
-from gpu_util import Packed, check_parity, row_l1_bound, run
+from gpu_util import Packed, check_parity, make_workspace, row_l1_bound, run
 
 pytestmark = pytest.mark.gpu
 
@@ -121,6 +121,21 @@ def test_special_values_in_x():
     x[1::97] = np.float16(6.0e-8)       # subnormal
     x[5::101] = np.float16(2048.0)
     check_parity(run(p, x, f32_out=True), _oracle_full(p, x), x, _bound(p), f32_out=True)
+
+
+def test_one_workspace_serves_many_calls_and_shapes():
+    # the arrival counters are left at zero by every call: a workspace prepared once is
+    # reused across calls, shapes, batch sizes and output types
+    ws = make_workspace(L.lutgemm_workspace_bytes(4100, 3072, 3, 128, 8, 4))
+    for (m, n, q, g, batch) in [(4100, 3072, 3, 128, None), (515, 2048, 2, 64, None), (4100, 3072, 3, 128, 4),
+                                (77, 520, 3, 0, None), (4100, 3072, 3, 128, None)]:
+        print(f"case m={m} n={n} q={q} g={g} batch={batch}", flush=True)
+        W = synth.weights_fp16(m, n, seed=4300 + m)
+        x = synth.activations_fp16(n, seed=4301 + m, batch=batch)
+        p = Packed.from_weights(W, q, g)
+        y = run(p, x, f32_out=True, workspace=ws)
+        np.testing.assert_array_equal(y, run(p, x, f32_out=True))
+        np.testing.assert_array_equal(y, run(p, x, f32_out=True, workspace=ws))
 
 
 def test_runs_on_a_side_stream():
