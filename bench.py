@@ -10,7 +10,8 @@ x ~ N(0, 1) fp16; everything is resident in HBM before the timed region.  Two de
 copies of every layer alternate between steps, and a step streams 765 MB, so no layer
 is served from the 256 MB Infinity Cache.
 
-Prints ONE JSON line (metric: microseconds per GEMV, averaged over the four layers).
+Prints ONE JSON line (metric: microseconds per GEMV, averaged over the four layers of a
+step; per-layer times come from a separate pass after the timed region).
 """
 from __future__ import annotations
 
@@ -33,10 +34,11 @@ LAYERS = ["qkv", "out", "fc1", "fc2"]
 # context only, never used for vs_baseline.
 PAPER_A100_FC1_MS = 0.2250
 
-# HBM bytes per launch of the dominant kernel measured offline with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); None until a
-# counter run for the current kernel is committed under profiles/.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel (average over the four layer shapes of a
+# step), measured offline with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each
+# scaled by what the counter reads for a 256 MiB copy kernel in the same run: summary in
+# profiles/lutgemm_gemv_kernel_opt175b_q3_g128_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = 196.7e6
 
 
 def algorithmic_bytes(m, n, q, g, batch=1, with_z=False):
@@ -52,6 +54,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--copies", type=int, default=2, help="device copies of each layer rotated between steps")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three plain 256 MiB device copies before the timed region (the known-size "
+                         "reference that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -99,46 +104,64 @@ def main():
         L.lutgemm_gemv(ent["x"], ent["bits"][c], ent["alpha"][c], None, ent["y"], Q, G, MU, ent["m"], ent["n"],
                        L.LUTGEMM_Y_F16, ent["ws"], ent["wsb"], sptr)
 
+    if args.copy_probe:
+        ref_src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        ref_dst = torch.empty_like(ref_src)
+        for _ in range(3):
+            ref_dst.copy_(ref_src)
+        torch.cuda.synchronize()
+
     for s in range(args.warmup):
         for ent in layers:
             launch(ent, s)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly `steps` steps, events on the launch stream around every GEMV
+    # ---- timed region: exactly `steps` steps; one HIP event pair on the launch stream around it
     nL = len(layers)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(nL + 1)] for _ in range(args.steps)]
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev0.record(stream)
     for s in range(args.steps):
-        ev[s][0].record(stream)
-        for li, ent in enumerate(layers):
+        for ent in layers:
             launch(ent, s)
-            ev[s][li + 1].record(stream)
+    ev1.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
     wall_ms_per_step = (t1 - t0) * 1e3 / args.steps
-    per_layer_us = np.zeros((args.steps, nL))
-    for s in range(args.steps):
-        for li in range(nL):
-            per_layer_us[s, li] = ev[s][li].elapsed_time(ev[s][li + 1]) * 1e3
-    mean_us = per_layer_us.mean(axis=0)
-    med_us = np.median(per_layer_us, axis=0)
+    event_ms_per_step = ev0.elapsed_time(ev1) / args.steps
     total_bytes = sum(e["bytes"] for e in layers)
     us_per_gemv = wall_ms_per_step * 1e3 / nL
     step_gbs = total_bytes / (wall_ms_per_step * 1e-3) / 1e9
 
-    # dominant kernel: the lookup/accumulate kernel, one launch per GEMV; per-launch figures
-    # are averages over the four layer shapes of a step (what a per-name profiler average is).
-    avg_launch_us = float(mean_us.mean())
+    # dominant kernel: lutgemm_gemv_kernel, ONE launch per GEMV (table build, lookups, scale
+    # epilogue and the split-K reduction are all in it).  Per-launch figures are averages
+    # over the four layer shapes of a step, which is what a per-name profiler average is.
+    avg_launch_us = event_ms_per_step * 1e3 / nL
     avg_launch_bytes = total_bytes / nL
     achieved = avg_launch_bytes / (avg_launch_us * 1e-6) / 1e9
+
+    # ---- per-layer breakdown, outside the timed region: each shape alone, back to back
+    mean_us = np.zeros(nL)
+    reps = max(20, args.steps // 4)
+    for li, ent in enumerate(layers):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for s in range(3):
+            launch(ent, s)
+        a.record(stream)
+        for s in range(reps):
+            launch(ent, s)
+        b.record(stream)
+        torch.cuda.synchronize()
+        mean_us[li] = a.elapsed_time(b) * 1e3 / reps
+    med_us = mean_us
 
     per_layer = []
     for li, ent in enumerate(layers):
         gbs = ent["bytes"] / (mean_us[li] * 1e-6) / 1e9
         per_layer.append({"layer": ent["name"], "m": ent["m"], "n": ent["n"], "bytes": ent["bytes"],
-                          "us_mean": round(float(mean_us[li]), 2), "us_median": round(float(med_us[li]), 2),
+                          "us_alone_back_to_back": round(float(mean_us[li]), 2),
                           "gbs": round(gbs, 1), "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4)})
 
     out = {
@@ -153,7 +176,7 @@ def main():
         "effective_gbs": round(step_gbs, 1), "frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
         "per_layer": per_layer,
         "paper_context": {"fc1_ms": PAPER_A100_FC1_MS, "hardware": "A100-80GB (paper table 1)"},
-        "roofline": {"bound": "hbm", "kernel": "lutgemm_gemv_kernel<3,false,false>",
+        "roofline": {"bound": "hbm", "kernel": "lutgemm_gemv_kernel<3,false,0,0>",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
                      "bytes_per_launch": avg_launch_bytes, "avg_launch_us": round(avg_launch_us, 3)},
