@@ -33,6 +33,7 @@ namespace {
 constexpr int kWaves = LUT_WAVES;
 constexpr int kThreads = kWaves * 64;
 constexpr int kLutBytes = 2 * 256 * 64 * 4;  // two sub-slabs x 256 keys x 64 lanes x fp32
+constexpr int kQueueWord = kLutBytes / 4;      // one extra LDS word after the tables: the workgroup's unit queue
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -271,28 +272,56 @@ __device__ __forceinline__ float compute_unit(const Unit<Q, 0, Q, T, AMODE, HAS_
   return quad_rows_reduce(acc, lane, row_in_block);
 }
 
-// Table build of one tile (section 3.1; appendix B: each block fills its tables first),
-// ending with the workgroup barrier that publishes the tables.
+// Table build of one tile (section 3.1; appendix B: each block fills its tables first).
+// Wavefront w builds key range [32*(w % 8), +32) of sub-slab (w / 8 + pass * kWaves / 8);
+// the activations are fetched first (fetch_tile_x) so that their latency overlaps whatever
+// the caller issues in between, and build_tile_tables ends with the workgroup barrier that
+// publishes the tables.
+constexpr int kBuildPasses = 16 / kWaves;   // table slots (sub-slab, key range) per wavefront at T = 2
+static_assert(16 % kWaves == 0 && kWaves >= 8, "8 or 16 wavefronts per workgroup");
+
 template <int T>
-__device__ __forceinline__ void build_tile_tables(const GemvParams& p, float* lut, int kt, int chunks_in_tile, int wave,
-                                                  int lane) {
-  for (int slot = wave; slot < T * 8; slot += kWaves) {
-    const int t = slot >> 3, kh = slot & 7;
-    const int cc = T * lane + t;
-    float xs[8];
-    if (cc < chunks_in_tile) {
-      const u32x4 raw = *reinterpret_cast<const u32x4*>(p.x + (int64_t)(128 * kt + cc) * 8);
-      xs[0] = half_lo(raw.x); xs[1] = half_hi(raw.x);
-      xs[2] = half_lo(raw.y); xs[3] = half_hi(raw.y);
-      xs[4] = half_lo(raw.z); xs[5] = half_hi(raw.z);
-      xs[6] = half_lo(raw.w); xs[7] = half_hi(raw.w);
-    } else {
+__device__ __forceinline__ void fetch_tile_x(const GemvParams& p, int kt, int chunks_in_tile, int wave, int lane,
+                                             u32x4 (&raw)[kBuildPasses]) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) xs[j] = 0.0f;
+  for (int b = 0; b < kBuildPasses; ++b) {
+    const int slot = wave + b * kWaves;
+    const int t = slot >> 3;
+    const int cc = min(T * lane + t, chunks_in_tile - 1);   // clamped: unconditional load, value unused if out of range
+    raw[b] = *reinterpret_cast<const u32x4*>(p.x + (int64_t)(128 * kt + cc) * 8);
+  }
+}
+
+template <int T>
+__device__ __forceinline__ void build_tile_tables(float* lut, int chunks_in_tile, int wave, int lane,
+                                                  const u32x4 (&raw)[kBuildPasses]) {
+#pragma unroll
+  for (int b = 0; b < kBuildPasses; ++b) {
+    const int slot = wave + b * kWaves;
+    if (slot < T * 8) {
+      const int t = slot >> 3, kh = slot & 7;
+      const bool live = T * lane + t < chunks_in_tile;
+      float xs[8];
+      xs[0] = half_lo(raw[b].x); xs[1] = half_hi(raw[b].x);
+      xs[2] = half_lo(raw[b].y); xs[3] = half_hi(raw[b].y);
+      xs[4] = half_lo(raw[b].z); xs[5] = half_hi(raw[b].z);
+      xs[6] = half_lo(raw[b].w); xs[7] = half_hi(raw[b].w);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) xs[j] = live ? xs[j] : 0.0f;   // empty slot: an all-zero table
+      build_tables(lut, t, kh, lane, xs);
     }
-    build_tables(lut, t, kh, lane, xs);
   }
   __syncthreads();
+}
+
+// Next unit of the workgroup's queue (wave-uniform).  Units are handed out in order, so the
+// workgroup still walks its slice of the packed weights front to back, but a wavefront that
+// runs ahead simply takes more of them: all wavefronts run dry within one unit of each other.
+__device__ __forceinline__ int next_unit(float* lut, int lane) {
+  int v = 0;
+  if (lane == 0)
+    v = __hip_atomic_fetch_add(reinterpret_cast<int*>(lut + kQueueWord), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  return __builtin_amdgcn_readfirstlane(v);
 }
 
 // Per-lane lookup constants: dword s of this lane looks into the table of slot
@@ -336,7 +365,9 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   if constexpr (Q > 4) {
     // ---- more than four planes: no fetch-ahead, each unit in two halves ----
     constexpr int QA = (Q + 1) / 2;
-    build_tile_tables<T>(p, lut, kt, chunks_in_tile, wave, lane);
+    u32x4 xraw[kBuildPasses];
+    fetch_tile_x<T>(p, kt, chunks_in_tile, wave, lane, xraw);
+    build_tile_tables<T>(lut, chunks_in_tile, wave, lane, xraw);
     uint32_t lane_base[4];
     float sum_x[4][T];
     lane_tables<T, HAS_Z>(lane, lane_base, sum_x);
@@ -353,56 +384,56 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
       store_device_coherent(partial + rb * 16 + row_in_block, s);
     }
   } else {
-  // Units of this wavefront: rb0 + wave + j * kWaves.  kDepth units are fetched ahead of
-  // the one being computed; the first fetches are issued before the tables are built, so
-  // that the HBM latency overlaps the build.  Fetches past the wavefront's last unit are
-  // redirected to the range's last row block (a harmless re-read) instead of branching.
+  // Units of the workgroup: u = 0 .. n_units-1 (row block rb0 + u).  A wavefront starts with
+  // unit `wave` and takes every further one from the queue.  With kDepth == 1 the next unit
+  // is fetched while the current one is computed; the first fetch is issued before the
+  // tables are built and AFTER the fetch of the activations (loads return in order, and the
+  // build must not wait for a whole unit of weights).  Fetches beyond the last unit are
+  // redirected to it (a harmless re-read) instead of branching, so that the wait counters
+  // stay exact and later fetches stay in flight.
+  static_assert(kDepth == 0 || kDepth == 1, "zero or one unit fetched ahead");
+  const int n_units = rb1 - rb0;
+  const int u_clamp = n_units - 1;
+  u32x4 xraw[kBuildPasses];
+  fetch_tile_x<T>(p, kt, chunks_in_tile, wave, lane, xraw);
+  if (threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = kWaves;   // units 0..kWaves-1 are taken
   U u[kDepth + 1];
-  const int rb_first = rb0 + wave;
-  const int rb_clamp = rb1 - 1;
-#pragma unroll
-  for (int d = 0; d < kDepth; ++d)
-    load_unit(u[d], p, tile_base, min(rb_first + d * kWaves, rb_clamp), lane, grp, partial, out_row, !first_tile);
+  int cur = wave;                               // unit being computed (or about to be)
+  if (kDepth == 1) load_unit(u[0], p, tile_base, rb0 + min(cur, u_clamp), lane, grp, partial, out_row, !first_tile);
 
-  build_tile_tables<T>(p, lut, kt, chunks_in_tile, wave, lane);
+  build_tile_tables<T>(lut, chunks_in_tile, wave, lane, xraw);
   uint32_t lane_base[4];
   float sum_x[4][T];
   lane_tables<T, HAS_Z>(lane, lane_base, sum_x);
 
-  // ---- lookup / accumulate over this workgroup's row blocks ----
-  // Four units per trip: the unit buffers rotate by name (kDepth + 1 divides 4), and the
-  // four results are parked in ONE register (unit j of the trip in lanes 16j..16j+15) and
-  // written by a single store after the fetches of the next trip have been issued.  A
-  // store shares the wave's memory counter with the loads, so an outstanding store issued
-  // BEFORE a load makes every wait for that load wait for the store's round trip as well;
-  // fewer stores, each younger than the loads in flight, keep that off the critical path.
-  static_assert(4 % (kDepth + 1) == 0, "the unit buffers must rotate with period 4");
+  // ---- lookup / accumulate ----
+  // Up to four results are parked in ONE register (the j-th of a trip in lanes 16j..16j+15)
+  // and written by a single store.  A store shares the wave's memory counter with the
+  // loads: an outstanding store issued BEFORE a load makes every wait for that load wait
+  // for the store's round trip too, so stores are few and younger than the loads in flight.
   const int lane_row = lane >> 4;
-  int rb = rb_first;
-  for (; rb + 3 * kWaves < rb1; rb += 4 * kWaves) {
+  while (cur < n_units) {
     float parked = 0.0f;
+    int parked_rb = 0, n_parked = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      // kDepth == 0: the unit itself, fetched just in time
-      load_unit(u[(j + kDepth) % (kDepth + 1)], p, tile_base, min(rb + (j + kDepth) * kWaves, rb_clamp), lane, grp,
-                partial, out_row, !first_tile);
+      int nxt = cur;
+      if (kDepth == 1) {
+        nxt = next_unit(lut, lane);
+        load_unit(u[(j + 1) & 1], p, tile_base, rb0 + min(nxt, u_clamp), lane, grp, partial, out_row, !first_tile);
+      } else {
+        load_unit(u[0], p, tile_base, rb0 + cur, lane, grp, partial, out_row, !first_tile);
+      }
       int row_in_block;
-      const float s = compute_unit(u[j % (kDepth + 1)], lane, lane_base, sum_x, &row_in_block) + u[j % (kDepth + 1)].prev;
+      const U& uc = u[kDepth == 1 ? (j & 1) : 0];
+      const float s = compute_unit(uc, lane, lane_base, sum_x, &row_in_block) + uc.prev;
       parked = (lane_row == j) ? s : parked;
+      parked_rb = (lane_row == j) ? rb0 + cur : parked_rb;
+      n_parked = j + 1;
+      cur = (kDepth == 1) ? nxt : next_unit(lut, lane);
+      if (cur >= n_units) break;
     }
-    store_device_coherent(partial + (rb + lane_row * kWaves) * 16 + out_row, parked);
-  }
-  // the last one to three units of this wavefront
-#pragma unroll
-  for (int j = 0; j < 3; ++j) {
-    const int rb_cur = rb + j * kWaves;
-    if (rb_cur >= rb1) break;
-    load_unit(u[(j + kDepth) % (kDepth + 1)], p, tile_base, min(rb_cur + kDepth * kWaves, rb_clamp), lane, grp,
-              partial, out_row, !first_tile);
-    int row_in_block;
-    const float s = compute_unit(u[j % (kDepth + 1)], lane, lane_base, sum_x, &row_in_block) + u[j % (kDepth + 1)].prev;
-    // the four rows of 16 lanes hold, and store, the same 16 sums
-    store_device_coherent(partial + rb_cur * 16 + row_in_block, s);
+    if (lane_row < n_parked) store_device_coherent(partial + parked_rb * 16 + out_row, parked);
   }
   }   // Q <= 4
 }
@@ -420,7 +451,7 @@ constexpr int prefetch_depth(int q, int amode) {
 // AM2 / AM1: scale modes of the two-sub-slab tiles and of a one-sub-slab last tile.
 template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
-  __shared__ float lut[kLutBytes / 4];
+  __shared__ float lut[kLutBytes / 4 + 4];
   // The lookup addresses are formed as if the tables start at LDS address 0.
   if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
   const int kg = blockIdx.x % p.KG;
@@ -452,11 +483,11 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
   }
   __syncthreads();
   if (flag[0] == 0u) return;
-  // Four rows per thread per pass, 16 K groups per row per batch: 64 independent loads in
+  // Eight rows per thread per pass, 16 K groups per row per batch: 128 independent loads in
   // flight per thread, because every one of them goes to memory (the partials were
   // written through by other workgroups).  Addresses are clamped, not predicated; the sum
   // over the groups of a row always runs in ascending group order.
-  constexpr int kRowsPerPass = 4;
+  constexpr int kRowsPerPass = 8;
   const int row_end = min(rb1 * 16, p.m);
   for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
     const float* src[kRowsPerPass];
