@@ -3,7 +3,7 @@
 // (paper section 3.1, section 3.2, appendix B), behind lutgemm_gemv / lutgemm_gemm.
 //
 // Mapping (this library's own; the paper's thread-block design was made for another GPU):
-//   * One workgroup of 8 wavefronts owns one K tile (1024 input columns = 128 tables
+//   * One workgroup of 16 wavefronts owns one K tile (1024 input columns = 128 tables
 //     of 256 fp32 entries = 128 KB of LDS) for a contiguous range of row blocks, so a
 //     table set is built once per workgroup and reused for thousands of rows.
 //   * Table (t, L) lives at LDS byte address  t<<16 | key<<8 | L<<2 : its 256 entries all
@@ -28,7 +28,7 @@
 namespace {
 
 #ifndef LUT_WAVES
-#define LUT_WAVES 8      // wavefronts per workgroup (two per SIMD: 256 registers each, no spilling)
+#define LUT_WAVES 16     // wavefronts per workgroup (four per SIMD: 128 registers each)
 #endif
 constexpr int kWaves = LUT_WAVES;
 constexpr int kThreads = kWaves * 64;
@@ -261,6 +261,22 @@ __device__ __forceinline__ void accumulate_unit(const Unit<Q, I0, QP, T, AMODE, 
   }
 }
 
+// Planes I0, I0+PP, ... of one unit, PP at a time: fetch, then accumulate.
+template <int Q, int I0, int PP, int T, int AMODE, bool HAS_Z>
+__device__ __forceinline__ void plane_passes(const GemvParams& p, int64_t tile_base, int rb, int lane,
+                                             const int (&grp)[4][T], const float* partial, int out_row, bool add_prev,
+                                             const uint32_t (&lane_base)[4], const float (&sum_x)[4][T], float (&acc)[4],
+                                             float* prev) {
+  constexpr int QP = (Q - I0 < PP) ? Q - I0 : PP;
+  Unit<Q, I0, QP, T, AMODE, HAS_Z> u;
+  load_unit(u, p, tile_base, rb, lane, grp, partial, out_row, add_prev);
+  accumulate_unit(u, lane_base, sum_x, acc);
+  if constexpr (I0 == 0) *prev = u.prev;
+  if constexpr (I0 + QP < Q)
+    plane_passes<Q, I0 + QP, PP, T, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, add_prev, lane_base, sum_x,
+                                                  acc, prev);
+}
+
 // Whole-unit compute for layers fetched in one piece.  Returns the 64-lane sum for the row
 // quad_rows_reduce assigns to this lane.
 template <int Q, int T, int AMODE, bool HAS_Z>
@@ -362,9 +378,12 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   // the row of the 16-row block whose sum this lane ends up with (see quad_rows_reduce)
   const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
 
-  if constexpr (Q > 4) {
-    // ---- more than four planes: no fetch-ahead, each unit in two halves ----
-    constexpr int QA = (Q + 1) / 2;
+  // Planes fetched together: all of them for up to four planes, about half for more; one
+  // at a time when every (dword, sub-slab) has a scale set of its own.  Keeps a wavefront
+  // within its registers in every variant.
+  constexpr int PP = (AMODE == kAlphaPerChunk) ? 1 : (Q > 4 ? (Q + 1) / 2 : Q);
+  if constexpr (PP < Q) {
+    // ---- several fetches per unit, no fetch-ahead ----
     u32x4 xraw[kBuildPasses];
     fetch_tile_x<T>(p, kt, chunks_in_tile, wave, lane, xraw);
     build_tile_tables<T>(lut, chunks_in_tile, wave, lane, xraw);
@@ -373,14 +392,11 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
     lane_tables<T, HAS_Z>(lane, lane_base, sum_x);
     for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
       float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      Unit<Q, 0, QA, T, AMODE, HAS_Z> ua;
-      load_unit(ua, p, tile_base, rb, lane, grp, partial, out_row, !first_tile);
-      accumulate_unit(ua, lane_base, sum_x, acc);
-      Unit<Q, QA, Q - QA, T, AMODE, HAS_Z> ub;
-      load_unit(ub, p, tile_base, rb, lane, grp, partial, out_row, !first_tile);
-      accumulate_unit(ub, lane_base, sum_x, acc);
+      float prev = 0.0f;
+      plane_passes<Q, 0, PP, T, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, !first_tile, lane_base, sum_x,
+                                              acc, &prev);
       int row_in_block;
-      const float s = quad_rows_reduce(acc, lane, &row_in_block) + ua.prev;
+      const float s = quad_rows_reduce(acc, lane, &row_in_block) + prev;
       store_device_coherent(partial + rb * 16 + row_in_block, s);
     }
   } else {
@@ -438,12 +454,15 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   }   // Q <= 4
 }
 
-// Units fetched ahead of the one being computed: one where two units fit the 256 registers
-// of a wavefront without spilling (any use of scratch memory costs far more than it hides).
+// Units fetched ahead of the one being computed.  With 16 wavefronts per workgroup the other
+// wavefronts cover a fetch, and nothing is fetched ahead; with 8 (256 registers each) one
+// unit is, where two units fit without spilling (any use of scratch memory costs far more
+// than a prefetch hides).
 constexpr int prefetch_depth(int q, int amode) {
 #ifdef LUT_DEPTH
   return LUT_DEPTH;
 #else
+  if (kWaves > 8) return 0;
   return (amode == kAlphaQuad && q <= 4) || (amode == kAlphaPerSlot && q <= 3) ? 1 : 0;   // q > 4: unused
 #endif
 }
@@ -487,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
   // flight per thread, because every one of them goes to memory (the partials were
   // written through by other workgroups).  Addresses are clamped, not predicated; the sum
   // over the groups of a row always runs in ascending group order.
-  constexpr int kRowsPerPass = 8;
+  constexpr int kRowsPerPass = (kWaves > 8) ? 2 : 8;   // bounded by the registers of a wavefront
   const int row_end = min(rb1 * 16, p.m);
   for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
     const float* src[kRowsPerPass];
