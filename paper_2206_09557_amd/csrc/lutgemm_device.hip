@@ -506,7 +506,7 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
   // flight per thread, because every one of them goes to memory (the partials were
   // written through by other workgroups).  Addresses are clamped, not predicated; the sum
   // over the groups of a row always runs in ascending group order.
-  constexpr int kRowsPerPass = (kWaves > 8) ? 2 : 8;   // bounded by the registers of a wavefront
+  constexpr int kRowsPerPass = (kWaves > 8) ? 3 : 8;   // bounded by the registers of a wavefront
   const int row_end = min(rb1 * 16, p.m);
   for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
     const float* src[kRowsPerPass];

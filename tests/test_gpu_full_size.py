@@ -1,7 +1,8 @@
-"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times:
-OPT-175B-shaped layers, q = 3, g = 128, batch 1.  The fp64 oracle computes a sample of
-output rows one by one (first and last row blocks, block boundaries of the row split,
-random rows); out-proj is compared on every row."""
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times:
+OPT-175B-shaped layers (q = 3, g = 128), OPT-13B-shaped layers (q = 4, g = 128) and
+LLaMA-65B-shaped layers with per-group offsets over a (q, g) sweep, batch 1.  The fp64
+oracle computes a sample of output rows one by one (first and last row blocks, block
+boundaries of the row splits, random rows); the 175B out-proj is compared on every row."""
 import numpy as np
 import pytest
 
@@ -53,3 +54,62 @@ def test_opt175b_layer_sampled_rows(name):
     np.testing.assert_array_equal(run(p, x, f32_out=True), y32)
     blocks = np.abs(y32[: (m // 256) * 256]).reshape(-1, 256).mean(axis=1)
     assert blocks.min() > 0.2 * np.median(blocks)
+
+
+def _check_layer(m, n, q, g, mode, seed, all_rows=False):
+    W = synth.weights_fp16(m, n, seed=seed)
+    x = synth.activations_fp16(n, seed=seed + 500)
+    p = Packed.from_weights(W, q, g, mode)
+    del W
+    y16 = run(p, x)
+    y32 = run(p, x, f32_out=True)
+    np.testing.assert_array_equal(y32.astype(np.float16), y16)
+    rows = None if all_rows else _sample_rows(m, np.random.default_rng(seed))
+    y_ref, _ = c_oracle.gemv_packed(p.bits, p.alpha, p.z, x, m, n, q, g, rows=rows)
+    gc = n if g == 0 else g
+    a = O.decode_alpha(p.alpha, m, n // gc, q)
+    z = None if p.z is None else O.decode_z(p.z, m, n // gc)
+    bound = row_l1_bound(a, z, gc)
+    sel = slice(None) if rows is None else rows
+    check_parity(y16[sel], y_ref, x, bound[sel])
+    check_parity(y32[sel], y_ref, x, bound[sel], f32_out=True)
+    assert np.all(np.isfinite(y32))
+    np.testing.assert_array_equal(run(p, x, f32_out=True), y32)
+
+
+@pytest.mark.parametrize("name", ["qkv", "out", "fc1", "fc2"])
+def test_opt13b_layer_sampled_rows(name):
+    m, n = synth.OPT_13B[name]
+    print(f"case opt13b {name} m={m} n={n} q=4 g=128", flush=True)
+    _check_layer(m, n, 4, 128, L.LUTGEMM_Q_GREEDY, seed=1000 + len(name) + m % 89)
+
+
+# (layer, q, g): the sweep q in {2,3,4} x g in {32,64,128,row-wise}, spread over the four
+# LLaMA-65B layer shapes; gate_up / down have n or m = 22016 = 21.5 tiles of 1024 columns.
+LLAMA_CASES = [("qkv", 3, 128), ("qkv", 2, 32), ("out", 4, 64), ("out", 2, 0), ("gate_up", 4, 128), ("gate_up", 3, 32),
+               ("gate_up", 2, 64), ("down", 3, 0), ("down", 4, 32), ("down", 3, 64), ("down", 2, 128), ("qkv", 4, 0)]
+
+
+@pytest.mark.parametrize("name,q,g", LLAMA_CASES)
+def test_llama65b_layer_with_offset_sampled_rows(name, q, g):
+    m, n = synth.LLAMA_65B[name]
+    print(f"case llama65b {name} m={m} n={n} q={q} g={g} uniform->BCQ with offset", flush=True)
+    _check_layer(m, n, q, g, L.LUTGEMM_Q_UNIFORM_RTN, seed=4000 + 7 * q + g + m % 83)
+
+
+def test_small_batch_on_fc1_shape():
+    # config 5 at reduced batch: every activation vector of a batch is an independent GEMV
+    m, n = synth.OPT_175B["fc1"]
+    q, g = 3, 128
+    print(f"case batch fc1 m={m} n={n}", flush=True)
+    W = synth.weights_fp16(m, n, seed=5000)
+    p = Packed.from_weights(W, q, g)
+    del W
+    X = synth.activations_fp16(n, seed=5500, batch=3)
+    Y = run(p, X, f32_out=True)
+    rows = _sample_rows(m, np.random.default_rng(5))
+    a = O.decode_alpha(p.alpha, m, n // g, q)
+    bound = row_l1_bound(a, None, g)
+    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g, rows=rows)
+    for b in range(3):
+        check_parity(Y[b][rows], Yref[b], X[b], bound[rows], f32_out=True)
