@@ -106,9 +106,9 @@ size_t lutgemm_bits_bytes(int64_t m, int64_t n, int q);
 size_t lutgemm_alpha_bytes(int64_t m, int64_t n, int q, int g);
 size_t lutgemm_z_bytes(int64_t m, int64_t n, int g);
 
-/* Device scratch a gemv/gemm call needs: 32 KB of arrival counters followed by the
-   split-K partial sums (the per-block partial outputs that appendix B accumulates
-   across thread blocks).  0 on invalid arguments.                                       */
+/* Device scratch a gemv/gemm call needs: 32 KB of arrival counters, 512 KB that take
+   results nobody reads, and the split-K partial sums (the per-block partial outputs that
+   appendix B accumulates across thread blocks).  0 on invalid arguments.                */
 size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch);
 
 /* DEVICE.  Enqueue the one-time preparation of a freshly allocated workspace (zeroes its
@@ -156,8 +156,13 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* As lutgemm_gemv for `batch` activation vectors (1 <= batch <= 32): x is fp16
-   [batch][n], y is [batch][m]; one table set per activation vector, each fetched key
-   serving all of them (the small-batch case discussed in section 6).                    */
+   [batch][n], y is [batch][m], workspace sized for this batch.  The vectors are taken two
+   at a time: one table set per activation vector, each fetched key looked up in both, so
+   the weights are streamed once per pair (the small-batch case discussed in section 6);
+   an odd last vector runs as a lutgemm_gemv.  Row v of y equals, bit for bit, what the
+   same call would give for any other batch that places vector v at an index of the same
+   parity role (paired or last-odd); it is within the documented tolerance of, but not
+   bitwise equal to, the lutgemm_gemv result.                                            */
 int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void* z, void* y,
                  int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                  void* workspace, size_t workspace_bytes, void* hip_stream);

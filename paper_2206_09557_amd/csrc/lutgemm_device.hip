@@ -56,6 +56,10 @@ struct GemvParams {
   int TPG;                // K tiles per K group
   int row_splits;         // workgroups along the rows
   int y_f32;              // output type
+  // pair kernel only
+  int n;                  // columns
+  int64_t vec_stride;     // floats between the partials of the two vectors of a pair
+  float* spare;           // [256 workgroup slots][16 wavefronts][2][16]: where results nobody reads are stored
 };
 
 // DPP controls (GFX9 encoding)
@@ -175,16 +179,20 @@ __device__ __forceinline__ void lane_groups(const GemvParams& p, int kt, int lan
 
 // All loads are unconditional (no branch between a fetch and the waits of the compute that
 // follows it), so that the wait counters let later fetches stay in flight.
-template <int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
+template <bool SUB = false, int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
 __device__ __forceinline__ void load_unit(Unit<Q, I0, QP, T, AMODE, HAS_Z>& u, const GemvParams& p, int64_t tile_base,
                                           int rb, int lane, const int (&grp)[4][T], const float* partial, int out_row,
-                                          bool add_prev) {
+                                          bool add_prev, int sub_T = T, int sub_t0 = 0) {
+  // SUB: the unit is ONE sub-slab (sub_t0) of a tile laid out with sub_T sub-slabs per plane
+  // (the pair kernel); otherwise all T sub-slabs of the tile are fetched.
   using U = Unit<Q, I0, QP, T, AMODE, HAS_Z>;
-  const u32x4* bp = reinterpret_cast<const u32x4*>(p.bits + tile_base + (int64_t)rb * Q * T * 1024) + lane;
+  const int tile_T = SUB ? sub_T : T;
+  const int t0 = SUB ? sub_t0 : 0;
+  const u32x4* bp = reinterpret_cast<const u32x4*>(p.bits + tile_base + (int64_t)rb * Q * tile_T * 1024) + lane;
 #pragma unroll
   for (int i = 0; i < QP; ++i)
 #pragma unroll
-    for (int t = 0; t < T; ++t) u.w[i][t] = __builtin_nontemporal_load(bp + ((I0 + i) * T + t) * 64);
+    for (int t = 0; t < T; ++t) u.w[i][t] = __builtin_nontemporal_load(bp + ((I0 + i) * tile_T + t0 + t) * 64);
 #pragma unroll
   for (int s = 0; s < U::NS; ++s)
 #pragma unroll
@@ -454,6 +462,69 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   }   // Q <= 4
 }
 
+// Cross-group reduction by the last workgroup to arrive for a row range, for NVEC activation
+// vectors (appendix B accumulates the per-block partial outputs with atomics; here the
+// groups are added in index order by whoever arrives last, so y is reproducible bit for bit).
+template <int NVEC>
+__device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut, int rs, int rb0, int rb1) {
+  __syncthreads();                 // every partial store has completed, every lookup is done: the table memory is free
+  uint32_t* flag = reinterpret_cast<uint32_t*>(lut);
+  if (threadIdx.x == 0) {
+    // Issued after the barrier, hence after the completion of every partial store of this
+    // workgroup (the barrier drains the store counters of all its wavefronts).
+    const uint32_t arrived = __hip_atomic_fetch_add(p.counters + rs, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    flag[0] = (arrived == (uint32_t)(p.KG - 1)) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (flag[0] == 0u) return;
+  // Several rows per thread per pass, 16 K groups per row per batch: many independent loads
+  // in flight per thread, because every one of them goes to memory (the partials were
+  // written through by other workgroups).  Addresses are clamped, not predicated; the sum
+  // over the groups of a row always runs in ascending group order.
+  constexpr int kRowsPerPass = (kWaves > 8) ? 3 : 8;   // bounded by the registers of a wavefront
+  const int row_end = min(rb1 * 16, p.m);
+#pragma unroll
+  for (int vec = 0; vec < NVEC; ++vec) {
+    const float* part = NVEC == 1 ? p.partial : p.partial + (int64_t)vec * p.vec_stride;
+    for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
+      const float* src[kRowsPerPass];
+      float sum[kRowsPerPass];
+#pragma unroll
+      for (int j = 0; j < kRowsPerPass; ++j) {
+        src[j] = part + min(r0 + j * kThreads, row_end - 1);
+        sum[j] = 0.0f;
+      }
+      for (int kb = 0; kb < p.KG; kb += 16) {
+        float v[kRowsPerPass][16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
+#pragma unroll
+          for (int j = 0; j < kRowsPerPass; ++j) v[j][u] = load_device_coherent(src[j] + off);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const bool live = kb + u < p.KG;
+#pragma unroll
+          for (int j = 0; j < kRowsPerPass; ++j) sum[j] += live ? v[j][u] : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kRowsPerPass; ++j) {
+        const int r = r0 + j * kThreads;
+        if (r < row_end) {
+          if (p.y_f32)
+            static_cast<float*>(p.y)[(int64_t)vec * p.m + r] = sum[j];
+          else   // fp16 output, nearest even (paper table 1)
+            static_cast<__half*>(p.y)[(int64_t)vec * p.m + r] = __float2half_rn(sum[j]);
+        }
+      }
+    }
+  }
+  if (threadIdx.x == 0)            // leave the counter at zero for the next call on this workspace
+    __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Units fetched ahead of the one being computed.  With 16 wavefronts per workgroup the other
 // wavefronts cover a fetch, and nothing is fetched ahead; with 8 (256 registers each) one
 // unit is, where two units fit without spilling (any use of scratch memory costs far more
@@ -489,61 +560,306 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
       tile_body<Q, 1, AM1, HAS_Z, prefetch_depth(Q, AM1)>(p, lut, kt, rb0, rb1, partial, ti == 0);
   }
 
-  // ---- cross-group reduction by the last workgroup to arrive for this row range ----
-  // (appendix B accumulates the per-block partial outputs with atomics; here the groups
-  // are added in index order by whoever arrives last, so y is reproducible bit for bit.)
-  __syncthreads();                 // every partial store has completed, every lookup is done: the table memory is free
-  uint32_t* flag = reinterpret_cast<uint32_t*>(lut);
-  if (threadIdx.x == 0) {
-    // Issued after the barrier, hence after the completion of every partial store of this
-    // workgroup (the barrier drains the store counters of all its wavefronts).
-    const uint32_t arrived = __hip_atomic_fetch_add(p.counters + rs, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    flag[0] = (arrived == (uint32_t)(p.KG - 1)) ? 1u : 0u;
+  finish_row_range<1>(p, lut, rs, rb0, rb1);
+}
+
+// ---------------------------------------------------------------------------------------
+// Two activation vectors per pass (small batch, section 6).  The tables of BOTH vectors for
+// one sub-slab (512 columns) fill the LDS, the two entries of a (slot, key) side by side:
+// byte address  (L / 32) << 16 | key << 8 | (L % 32) << 3 | v << 2,  so that ONE 8-byte
+// lookup returns the partial sums of both vectors (a wavefront's 64 lookups still fall in
+// distinct banks: 32 lanes x 8 consecutive bytes per half).  The weights are streamed once
+// per pair; lookups and table builds double per byte of weights, which is the limitation
+// the paper states for growing batch.  K is split over "half tiles" (K tile, sub-slab);
+// a unit is (half tile, row block).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+#ifndef LUT_PAIR_DEPTH
+#define LUT_PAIR_DEPTH 1
+#endif
+constexpr int kPairDepth = LUT_PAIR_DEPTH;
+#ifndef LUT_STORE_LAG
+#define LUT_STORE_LAG 1
+#endif
+constexpr int kStoreLag = LUT_STORE_LAG;
+static_assert(kStoreLag == 0 || kStoreLag == 1, "results are stored at once or one unit later");
+
+__device__ __forceinline__ f32x2 lds_f32x2(uint32_t byte_addr) {
+  return *(const __attribute__((address_space(3))) f32x2*)(uintptr_t)byte_addr;
+}
+
+__device__ __forceinline__ void unpack_x(const u32x4& raw, bool live, float (&xs)[8]) {
+  xs[0] = half_lo(raw.x); xs[1] = half_hi(raw.x);
+  xs[2] = half_lo(raw.y); xs[3] = half_hi(raw.y);
+  xs[4] = half_lo(raw.z); xs[5] = half_hi(raw.z);
+  xs[6] = half_lo(raw.w); xs[7] = half_hi(raw.w);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) xs[j] = live ? xs[j] : 0.0f;   // empty slot: an all-zero table
+}
+
+// Entries of keys [kh*32 + hi*16, +16) of one table (section 3.1), by doubling.
+__device__ __forceinline__ void table_entries16(int kh, int hi, const float (&xs)[8], float (&e)[16]) {
+  float base = -(xs[0] + xs[1] + xs[2] + xs[3]);
+  base += hi ? xs[4] : -xs[4];
+#pragma unroll
+  for (int j = 5; j < 8; ++j) base += ((kh >> (j - 5)) & 1) ? xs[j] : -xs[j];
+  e[0] = base;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float two_x = 2.0f * xs[j];
+#pragma unroll
+    for (int k = 0; k < (1 << j); ++k) e[k + (1 << j)] = e[k] + two_x;
+  }
+}
+
+template <int Q, int I0, int QP, int AMODE, bool HAS_Z>
+__device__ __forceinline__ void accumulate_pair(const Unit<Q, I0, QP, 1, AMODE, HAS_Z>& u, const uint32_t (&lane_base)[4],
+                                                const f32x2 (&sum_x)[4], float (&acc)[2][4]) {
+  using U = Unit<Q, I0, QP, 1, AMODE, HAS_Z>;
+#pragma unroll
+  for (int i = 0; i < QP; ++i) {
+#pragma unroll
+    for (int rho = 0; rho < 4; ++rho) {
+      // address bytes {0, L / 32, key byte rho, (L % 32) * 8}: lane_base holds bytes 0 and 2 (as its bytes 0 and 1)
+      const uint32_t sel = 0x0c010000u | ((4u + rho) << 8);
+      float run0 = 0.0f, run1 = 0.0f;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const f32x2 e = lds_f32x2(__builtin_amdgcn_perm(u.w[i][0][s], lane_base[s], sel));
+        const bool first = (AMODE == kAlphaQuad) ? (s == 0) : true;
+        run0 = first ? e.x : run0 + e.x;
+        run1 = first ? e.y : run1 + e.y;
+        if (AMODE != kAlphaQuad || s == 3) {   // section 3.2 rule 2: one scale per run of lookups
+          const float a = half_of(u.al[(AMODE == kAlphaQuad) ? 0 : s][0][i], rho);
+          acc[0][rho] = fmaf(a, run0, acc[0][rho]);
+          acc[1][rho] = fmaf(a, run1, acc[1][rho]);
+        }
+      }
+    }
+  }
+  if (HAS_Z && I0 == 0) {   // offset term of eq. 3
+#pragma unroll
+    for (int s = 0; s < U::NS; ++s) {
+      f32x2 sx = sum_x[s];
+      if (AMODE == kAlphaQuad) sx = (sum_x[0] + sum_x[1]) + (sum_x[2] + sum_x[3]);
+#pragma unroll
+      for (int rho = 0; rho < 4; ++rho) {
+        const float zf = half_of(u.zz[s][0], rho);
+        acc[0][rho] = fmaf(zf, sx.x, acc[0][rho]);
+        acc[1][rho] = fmaf(zf, sx.y, acc[1][rho]);
+      }
+    }
+  }
+}
+
+template <int Q, int I0, int PP, int AMODE, bool HAS_Z>
+__device__ __forceinline__ void pair_passes(const GemvParams& p, int64_t tile_base, int rb, int lane, const int (&grp)[4][1],
+                                            const float* partial, int out_row, int tile_T, int t0,
+                                            const uint32_t (&lane_base)[4], const f32x2 (&sum_x)[4], float (&acc)[2][4]) {
+  constexpr int QP = (Q - I0 < PP) ? Q - I0 : PP;
+  Unit<Q, I0, QP, 1, AMODE, HAS_Z> u;
+  load_unit<true>(u, p, tile_base, rb, lane, grp, partial, out_row, false, tile_T, t0);
+  accumulate_pair(u, lane_base, sum_x, acc);
+  if constexpr (I0 + QP < Q)
+    pair_passes<Q, I0 + QP, PP, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, tile_T, t0, lane_base, sum_x, acc);
+}
+
+// One workgroup, one half tile (kt, t0), row blocks [rb0, rb1).  kDepth as in tile_body.
+template <int Q, int AMODE, bool HAS_Z, int kDepth>
+__device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, int kt, int t0, int rb0, int rb1,
+                                               float* partial, bool first_tile) {
+  using U = Unit<Q, 0, Q, 1, AMODE, HAS_Z>;
+  int lane = threadIdx.x & 63;
+  asm volatile("" : "+v"(lane));   // see tile_body
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
+  const int tile_T = chunks_in_tile > 64 ? 2 : 1;
+  const int64_t tile_base = (int64_t)kt * p.RB * Q * 2048;
+  const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
+  float* partial1 = partial + p.vec_stride;
+
+  int grp[4][1];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int slot = (lane & ~3) | ((s + lane) & 3);
+    grp[s][0] = ((128 * kt + min(tile_T * slot + t0, chunks_in_tile - 1)) * 8) / p.g;
+  }
+
+  // ---- activations of this lane's slot, both vectors (fetched before anything else) ----
+  const int my_chunk = tile_T * lane + t0;
+  const __half* xp = p.x + (int64_t)(128 * kt + min(my_chunk, chunks_in_tile - 1)) * 8;
+  const u32x4 xraw0 = *reinterpret_cast<const u32x4*>(xp);
+  const u32x4 xraw1 = *reinterpret_cast<const u32x4*>(xp + p.n);
+
+  constexpr int PP = Q > 4 ? (Q + 1) / 2 : Q;
+  // Units fetched ahead (D): as many as the registers of a wavefront hold, up to kDepth.  A
+  // unit is the key words plus a scale set (and offsets) per dword when the scales are not
+  // shared by the quad.  A unit is only 1 KB per plane, so it takes two of them in flight
+  // per wavefront to cover the memory latency at full bandwidth.
+  constexpr int kUnitRegs = 4 * Q + (AMODE == kAlphaQuad ? 2 * Q : 8 * Q + (HAS_Z ? 8 : 0));
+  constexpr int kFit = (PP < Q || kUnitRegs > 36) ? 0 : (kUnitRegs > 24 ? 1 : 2);
+  constexpr int D = kFit < kDepth ? kFit : kDepth;
+  const int n_units = rb1 - rb0;
+  const int u_clamp = n_units - 1;
+  // Ring of D + 1 units; uid[k]: the unit (row block rb0 + uid) in slot k.  A wavefront starts
+  // with units wave, wave + kWaves, ... and takes every further one from the queue.
+  U u[D + 1];
+  float prev1[D + 1];
+  int uid[D + 1];
+  if (PP == Q && threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = (D > 0 ? D : 1) * kWaves;
+#pragma unroll
+  for (int k = 0; k <= D; ++k) uid[k] = wave + k * kWaves;
+  if (PP == Q) {
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+      const int rb = rb0 + min(uid[k], u_clamp);
+      load_unit<true>(u[k], p, tile_base, rb, lane, grp, partial, out_row, !first_tile, tile_T, t0);
+      prev1[k] = !first_tile ? load_device_coherent(partial1 + rb * 16 + out_row) : 0.0f;
+    }
+  }
+
+  // ---- tables: build slot b (of 16) = 16 keys [32 * (b % 8) + 16 * (b / 8), +16) of both vectors ----
+  {
+    float xa[8], xb[8];
+    unpack_x(xraw0, my_chunk < chunks_in_tile, xa);
+    unpack_x(xraw1, my_chunk < chunks_in_tile, xb);
+    f32x2* dst = reinterpret_cast<f32x2*>(lut) + ((lane >> 5) << 13) + (lane & 31);
+#pragma unroll
+    for (int b = 0; b < kBuildPasses; ++b) {
+      const int slot = wave + b * kWaves;
+      const int kh = slot & 7, hi = slot >> 3;
+      float ea[16], eb[16];
+      table_entries16(kh, hi, xa, ea);
+      table_entries16(kh, hi, xb, eb);
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        f32x2 e;
+        e.x = ea[k];
+        e.y = eb[k];
+        dst[(kh * 32 + hi * 16 + k) << 5] = e;
+      }
+    }
   }
   __syncthreads();
-  if (flag[0] == 0u) return;
-  // Eight rows per thread per pass, 16 K groups per row per batch: 128 independent loads in
-  // flight per thread, because every one of them goes to memory (the partials were
-  // written through by other workgroups).  Addresses are clamped, not predicated; the sum
-  // over the groups of a row always runs in ascending group order.
-  constexpr int kRowsPerPass = (kWaves > 8) ? 3 : 8;   // bounded by the registers of a wavefront
-  const int row_end = min(rb1 * 16, p.m);
-  for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
-    const float* src[kRowsPerPass];
-    float sum[kRowsPerPass];
+
+  uint32_t lane_base[4];
+  f32x2 sum_x[4];
 #pragma unroll
-    for (int j = 0; j < kRowsPerPass; ++j) {
-      src[j] = p.partial + min(r0 + j * kThreads, row_end - 1);
-      sum[j] = 0.0f;
-    }
-    for (int kb = 0; kb < p.KG; kb += 16) {
-      float v[kRowsPerPass][16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
-#pragma unroll
-        for (int j = 0; j < kRowsPerPass; ++j) v[j][u] = load_device_coherent(src[j] + off);
+  for (int s = 0; s < 4; ++s) {
+    const uint32_t slot = ((uint32_t)lane & ~3u) | ((uint32_t)(s + lane) & 3u);
+    lane_base[s] = ((slot & 31u) << 3) | ((slot >> 5) << 8);
+    f32x2 zero;
+    zero.x = 0.0f;
+    zero.y = 0.0f;
+    sum_x[s] = HAS_Z ? lds_f32x2(((slot >> 5) << 16) | (0xffu << 8) | ((slot & 31u) << 3)) : zero;
+  }
+
+  if constexpr (PP < Q) {
+    for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
+      float acc[2][4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+      float pv0 = 0.0f, pv1 = 0.0f;
+      if (!first_tile) {
+        pv0 = load_device_coherent(partial + rb * 16 + out_row);
+        pv1 = load_device_coherent(partial1 + rb * 16 + out_row);
       }
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const bool live = kb + u < p.KG;
-#pragma unroll
-        for (int j = 0; j < kRowsPerPass; ++j) sum[j] += live ? v[j][u] : 0.0f;
-      }
+      pair_passes<Q, 0, PP, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, tile_T, t0, lane_base, sum_x, acc);
+      int row_in_block;
+      const float s0 = quad_rows_reduce(acc[0], lane, &row_in_block) + pv0;
+      const float s1 = quad_rows_reduce(acc[1], lane, &row_in_block) + pv1;
+      store_device_coherent(partial + rb * 16 + row_in_block, s0);
+      store_device_coherent(partial1 + rb * 16 + row_in_block, s1);
     }
+  } else {
+    // Dynamic unit queue (see tile_body), D units fetched ahead, D + 1 units per pass of the
+    // loop, ONE loop exit at the bottom: an exit in mid-loop would give the compiler a path
+    // that carries an unused fetch back to the loop head, and with it a wait for all memory
+    // traffic, stores included, on every pass.  A wavefront that finds the queue empty part
+    // way through a pass still fetches (the last unit, again) and stores (to a spare area
+    // nobody reads) but skips the lookups.  Results are kept for kStoreLag more units and
+    // stored right after a fetch has been issued (a store shares the wavefront's memory
+    // counter with the fetches; see tile_body), by all four 16-lane groups (same address,
+    // same value).  The spare area has 128 bytes per wavefront: one spare line for all would
+    // serialise every wavefront of the device on one memory channel.
+    if (uid[0] >= n_units) return;
+    float* const spare0 = p.spare + ((blockIdx.x & 255) * 16 + wave) * 32;
+    constexpr int kHeld = kStoreLag > 0 ? kStoreLag : 1;
+    float held0[kHeld], held1[kHeld];
+    float* held_to[kHeld];     // wave-uniform; the second vector's result goes held_step further
+    int64_t held_step[kHeld];
 #pragma unroll
-    for (int j = 0; j < kRowsPerPass; ++j) {
-      const int r = r0 + j * kThreads;
-      if (r < row_end) {
-        if (p.y_f32)
-          static_cast<float*>(p.y)[r] = sum[j];
-        else
-          static_cast<__half*>(p.y)[r] = __float2half_rn(sum[j]);   // fp16 output, nearest even (paper table 1)
+    for (int k = 0; k < kHeld; ++k) {
+      held0[k] = 0.0f;
+      held1[k] = 0.0f;
+      held_to[k] = spare0;
+      held_step[k] = 16;
+    }
+    do {
+#pragma unroll
+      for (int j = 0; j <= D; ++j) {
+        constexpr int kRing = D + 1;
+        const int fill = (j + D) % kRing;   // the slot consumed one pass of j ago (for D == 0: this one)
+        if (D > 0) uid[fill] = next_unit(lut, lane);
+        {
+          const int rb = rb0 + min(uid[fill], u_clamp);
+          load_unit<true>(u[fill], p, tile_base, rb, lane, grp, partial, out_row, !first_tile, tile_T, t0);
+          prev1[fill] = !first_tile ? load_device_coherent(partial1 + rb * 16 + out_row) : 0.0f;
+        }
+        constexpr int hs = 0;
+        if (kStoreLag > 0) {
+          store_device_coherent(held_to[hs] + out_row, held0[hs]);
+          store_device_coherent(held_to[hs] + held_step[hs] + out_row, held1[hs]);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // fetch and stores stay ahead of the lookups below
+        const bool real = uid[j] < n_units;
+        if (real) {
+          float acc[2][4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
+          accumulate_pair(u[j], lane_base, sum_x, acc);
+          int row_in_block;
+          held0[hs] = quad_rows_reduce(acc[0], lane, &row_in_block) + u[j].prev;
+          held1[hs] = quad_rows_reduce(acc[1], lane, &row_in_block) + prev1[j];
+        }
+        held_to[hs] = real ? partial + (rb0 + uid[j]) * 16 : spare0;
+        held_step[hs] = real ? p.vec_stride : 16;
+        if (kStoreLag == 0) {
+          store_device_coherent(held_to[hs] + out_row, held0[hs]);
+          store_device_coherent(held_to[hs] + held_step[hs] + out_row, held1[hs]);
+        }
+        if (D == 0) uid[0] = next_unit(lut, lane);
+      }
+    } while (uid[0] < n_units);
+    if (kStoreLag > 0) {
+#pragma unroll
+      for (int k = 0; k < kHeld; ++k) {
+        store_device_coherent(held_to[k] + out_row, held0[k]);
+        store_device_coherent(held_to[k] + held_step[k] + out_row, held1[k]);
       }
     }
   }
-  if (threadIdx.x == 0)            // leave the counter at zero for the next call on this workspace
-    __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// p.NT counts HALF tiles here; half tile h is sub-slab h % 2 of K tile h / 2 (a last tile
+// with one sub-slab contributes one half tile).  AM2 / AM1 as in the GEMV kernel.
+
+template <int Q, bool HAS_Z, int AM2, int AM1>
+__global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
+  __shared__ float lut[kLutBytes / 4 + 4];
+  if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
+  const int kg = blockIdx.x % p.KG;
+  const int rs = blockIdx.x / p.KG;
+  const int rb0 = (int)((int64_t)p.RB * rs / p.row_splits);
+  const int rb1 = (int)((int64_t)p.RB * (rs + 1) / p.row_splits);
+  float* partial = p.partial + (int64_t)kg * p.kg_stride;
+  for (int ti = 0; ti < p.TPG; ++ti) {
+    const int h = kg * p.TPG + ti;
+    if (h >= p.NT) break;
+    if (ti > 0) __syncthreads();
+    const int kt = h >> 1, t0 = h & 1;
+    if (min(128, p.nchunks - 128 * kt) > 64)
+      pair_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, rb0, rb1, partial, ti == 0);
+    else
+      pair_tile_body<Q, AM1, HAS_Z, kPairDepth>(p, lut, kt, t0, rb0, rb1, partial, ti == 0);
+  }
+  finish_row_range<2>(p, lut, rs, rb0, rb1);
 }
 
 // Zero the arrival counters of a fresh workspace.
@@ -583,6 +899,39 @@ GemvKernel pick_mode(int q, int64_t g) {
 
 GemvKernel pick_kernel(int q, bool has_z, int64_t g) {
   return has_z ? pick_mode<true>(q, g) : pick_mode<false>(q, g);
+}
+
+// Pair kernel: a lane's dword is one chunk, so the per-chunk scale mode does not occur.
+template <bool HAS_Z, int AM2, int AM1>
+GemvKernel pick_pair_q(int q) {
+#ifdef LUT_ONLY_Q
+  return q == LUT_ONLY_Q ? lutgemm_pair_kernel<LUT_ONLY_Q, HAS_Z, AM2, AM1> : nullptr;
+#else
+  switch (q) {
+    case 1: return lutgemm_pair_kernel<1, HAS_Z, AM2, AM1>;
+    case 2: return lutgemm_pair_kernel<2, HAS_Z, AM2, AM1>;
+    case 3: return lutgemm_pair_kernel<3, HAS_Z, AM2, AM1>;
+    case 4: return lutgemm_pair_kernel<4, HAS_Z, AM2, AM1>;
+    case 5: return lutgemm_pair_kernel<5, HAS_Z, AM2, AM1>;
+    case 6: return lutgemm_pair_kernel<6, HAS_Z, AM2, AM1>;
+    case 7: return lutgemm_pair_kernel<7, HAS_Z, AM2, AM1>;
+    case 8: return lutgemm_pair_kernel<8, HAS_Z, AM2, AM1>;
+  }
+  return nullptr;
+#endif
+}
+
+template <bool HAS_Z>
+GemvKernel pick_pair_mode(int q, int64_t g) {
+  // quad mode needs the quad's four chunks of one sub-slab in one group: they span 56 columns
+  // of an aligned 64 in a two-sub-slab tile, 32 columns in a one-sub-slab tile
+  if (g % 64 == 0) return pick_pair_q<HAS_Z, kAlphaQuad, kAlphaQuad>(q);
+  if (g % 32 == 0) return pick_pair_q<HAS_Z, kAlphaPerSlot, kAlphaQuad>(q);
+  return pick_pair_q<HAS_Z, kAlphaPerSlot, kAlphaPerSlot>(q);
+}
+
+GemvKernel pick_pair_kernel(int q, bool has_z, int64_t g) {
+  return has_z ? pick_pair_mode<true>(q, g) : pick_pair_mode<false>(q, g);
 }
 
 int compute_units() {
@@ -627,7 +976,52 @@ void choose_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
   }
 }
 
+// The same choice for the pair kernel (NT counts half tiles).  Costs in units of one round
+// of units of a workgroup: a table build is worth about 1.75 of them; the final reduction
+// runs in batches (rows of a range per pass of the workgroup x 16 K groups x 2 vectors) of
+// about 1.25 each, which is what rules out one half tile per group on wide layers.
+void choose_pair_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
+  double best = 1e30;
+  const int max_rs = (RB + kWaves - 1) / kWaves;
+  const int rows_per_pass = ((kWaves > 8) ? 3 : 8) * kThreads;   // kRowsPerPass of the final reduction
+  for (int tpg = 1; tpg <= NT && tpg <= 8; ++tpg) {
+    const int kg = (NT + tpg - 1) / tpg;
+    int rs = cus / kg;
+    rs = rs < 1 ? 1 : (rs > max_rs ? max_rs : rs);
+    const int blocks = (RB + rs - 1) / rs;
+    const int rounds = (blocks + kWaves - 1) / kWaves;
+    const int tiles = (NT + kg - 1) / kg;
+    const int passes = (blocks * 16 + rows_per_pass - 1) / rows_per_pass;
+    const double cost = tiles * (rounds + 1.75) + 1.25 * 2 * passes * ((kg + 15) / 16);
+    if (cost < best) {
+      best = cost;
+      *KG = kg;
+      *TPG = tpg;
+      *RS = rs;
+    }
+  }
+}
+
+// choose_grid plus the tuning overrides (environment variables, for sweeps).
+void plan_grid(int cus, bool pair, const char* tpg_var, const char* rs_var, GemvParams* p) {
+  const int wgs = cus > 256 ? 256 : cus;
+  if (pair)
+    choose_pair_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
+  else
+    choose_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
+  const int tpg = env_int(tpg_var), rs = env_int(rs_var);
+  const int max_rs = (p->RB + kWaves - 1) / kWaves;
+  if (tpg > 0) {
+    p->TPG = tpg > p->NT ? p->NT : tpg;
+    p->KG = (p->NT + p->TPG - 1) / p->TPG;
+    p->row_splits = wgs / p->KG;
+    p->row_splits = p->row_splits < 1 ? 1 : (p->row_splits > max_rs ? max_rs : p->row_splits);
+  }
+  if (rs > 0) p->row_splits = rs > 256 ? 256 : (rs > p->RB ? p->RB : rs);
+}
+
 constexpr size_t kCounterBytes = 32768;   // 32 activation vectors x 256 row ranges
+constexpr size_t kSpareBytes = 256 * 16 * 32 * sizeof(float);   // 128 bytes per (workgroup slot, wavefront)
 
 }  // namespace
 
@@ -675,18 +1069,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.NG = (int)(n / gg);
   p.g = (int)gg;
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
-  choose_grid(cus > 256 ? 256 : cus, p.NT, p.RB, &p.KG, &p.TPG, &p.row_splits);
-  {  // tuning overrides for sweeps
-    const int tpg = env_int("LUTGEMM_TPG"), rs = env_int("LUTGEMM_RS");
-    const int max_rs = (p.RB + kWaves - 1) / kWaves;
-    if (tpg > 0) {
-      p.TPG = tpg > p.NT ? p.NT : tpg;
-      p.KG = (p.NT + p.TPG - 1) / p.TPG;
-      p.row_splits = (cus > 256 ? 256 : cus) / p.KG;
-      p.row_splits = p.row_splits < 1 ? 1 : (p.row_splits > max_rs ? max_rs : p.row_splits);
-    }
-    if (rs > 0) p.row_splits = rs > 256 ? 256 : (rs > p.RB ? p.RB : rs);
-  }
+  plan_grid(cus, false, "LUTGEMM_TPG", "LUTGEMM_RS", &p);
   const int64_t m_pad = (int64_t)p.RB * 16;
   p.kg_stride = m_pad * batch;
 
@@ -694,18 +1077,34 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   if (!kern) return LUTGEMM_EUNSUPPORTED;
 
   uint32_t* counters = static_cast<uint32_t*>(workspace);
-  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
-  for (int b = 0; b < batch; ++b) {
-    GemvParams pb = p;
+  p.spare = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
+  p.n = (int)n;
+  p.vec_stride = m_pad;
+  const size_t y_elem = p.y_f32 ? sizeof(float) : sizeof(__half);
+
+  // Activation vectors two at a time (one stream of the weights per pair), a last odd one alone.
+  GemvParams pp = p;   // grid of the pair kernel: half tiles instead of tiles
+  GemvKernel pair_kern = nullptr;
+  if (batch >= 2) {
+    const int last_chunks = p.nchunks - 128 * (p.NT - 1);
+    pp.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);
+    plan_grid(cus, true, "LUTGEMM_PAIR_TPG", "LUTGEMM_PAIR_RS", &pp);
+    pair_kern = pick_pair_kernel(q, z != nullptr, gg);
+    if (!pair_kern) return LUTGEMM_EUNSUPPORTED;
+  }
+  for (int b = 0; b < batch;) {
+    const bool pair = b + 1 < batch;
+    GemvParams pb = pair ? pp : p;
     pb.x = static_cast<const __half*>(x) + (int64_t)b * n;
     pb.partial = partials + (int64_t)b * m_pad;
     pb.counters = counters + (int64_t)b * 256;
-    pb.y = p.y_f32 ? static_cast<void*>(static_cast<float*>(y) + (int64_t)b * m)
-                   : static_cast<void*>(static_cast<__half*>(y) + (int64_t)b * m);
+    pb.y = static_cast<char*>(y) + (int64_t)b * m * y_elem;
     void* args[] = {&pb};
-    if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.KG * p.row_splits), dim3(kThreads), args, 0,
-                        stream) != hipSuccess)
+    if (hipLaunchKernel(reinterpret_cast<const void*>(pair ? pair_kern : kern), dim3(pb.KG * pb.row_splits),
+                        dim3(kThreads), args, 0, stream) != hipSuccess)
       return LUTGEMM_EHIP;
+    b += pair ? 2 : 1;
   }
   return LUTGEMM_OK;
 }
