@@ -38,7 +38,7 @@ PAPER_A100_FC1_MS = 0.2250
 # step), measured offline with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each
 # scaled by what the counter reads for a 256 MiB copy kernel in the same run: summary in
 # profiles/lutgemm_gemv_kernel_opt175b_q3_g128_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = 196.7e6
+MEASURED_TRAFFIC_BYTES = 195.0e6
 
 
 def algorithmic_bytes(m, n, q, g, batch=1, with_z=False):
@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-batch-sweep", action="store_true", help="skip the FC1 small-batch pass")
     ap.add_argument("--copies", type=int, default=2, help="device copies of each layer rotated between steps")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 256 MiB device copies before the timed region (the known-size "
@@ -164,6 +165,33 @@ def main():
                           "us_alone_back_to_back": round(float(mean_us[li]), 2),
                           "gbs": round(gbs, 1), "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4)})
 
+    # ---- small batch on the FC1 shape (section 6 of the paper), outside the timed region ----
+    fc1 = layers[2]
+    batch_sweep = []
+    for b in (() if args.no_batch_sweep else (1, 2, 4, 8, 16, 32)):
+        xb = torch.randn(b, fc1["n"], device="cuda", generator=torch.Generator(device="cuda").manual_seed(77)).half()
+        yb = torch.empty(b, fc1["m"], dtype=torch.float16, device="cuda")
+        wsb = L.lutgemm_workspace_bytes(fc1["m"], fc1["n"], Q, G, batch=b)
+        wsg = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        L.lutgemm_workspace_init(wsg, wsb, sptr)
+
+        def gemm(step):
+            c = step % args.copies
+            L.lutgemm_gemm(xb, fc1["bits"][c], fc1["alpha"][c], None, yb, Q, G, MU, fc1["m"], fc1["n"], b,
+                           L.LUTGEMM_Y_F16, wsg, wsb, sptr)
+
+        for s in range(3):
+            gemm(s)
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for s in range(20):
+            gemm(s)
+        e.record(stream)
+        torch.cuda.synchronize()
+        us = a.elapsed_time(e) * 1e3 / 20
+        batch_sweep.append({"batch": b, "us": round(us, 2), "us_per_vector": round(us / b, 2)})
+        del xb, yb, wsg
+
     out = {
         "metric": "us/GEMV + achieved HBM GB/s (% roofline), OPT-175B-shape q=3 g=128 batch 1",
         "value": round(us_per_gemv, 3), "unit": "us/GEMV",
@@ -175,6 +203,7 @@ def main():
                    "gemvs_per_step": nL, "weight_copies_rotated": args.copies},
         "effective_gbs": round(step_gbs, 1), "frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
         "per_layer": per_layer,
+        "fc1_batch_sweep": batch_sweep,
         "paper_context": {"fc1_ms": PAPER_A100_FC1_MS, "hardware": "A100-80GB (paper table 1)"},
         "roofline": {"bound": "hbm", "kernel": "lutgemm_gemv_kernel<3,false,0,0>",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
