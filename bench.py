@@ -165,7 +165,8 @@ def main():
                           "us_alone_back_to_back": round(float(mean_us[li]), 2),
                           "gbs": round(gbs, 1), "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4)})
 
-    # ---- small batch on the FC1 shape (section 6 of the paper), outside the timed region ----
+    # ---- small batch on the FC1 shape (section 6 of the paper), outside the timed region:
+    # the lookup path (lutgemm_gemm) and the matrix-core path (lutgemm_gemm_mfma) side by side ----
     fc1 = layers[2]
     batch_sweep = []
     for b in (() if args.no_batch_sweep else (1, 2, 4, 8, 16, 32)):
@@ -189,7 +190,22 @@ def main():
         e.record(stream)
         torch.cuda.synchronize()
         us = a.elapsed_time(e) * 1e3 / 20
-        batch_sweep.append({"batch": b, "us": round(us, 2), "us_per_vector": round(us / b, 2)})
+
+        def gemm_mfma(step):   # the matrix-core path on the same buffers (no table lookups)
+            c = step % args.copies
+            L.lutgemm_gemm_mfma(xb, fc1["bits"][c], fc1["alpha"][c], None, yb, Q, G, MU, fc1["m"], fc1["n"], b,
+                                L.LUTGEMM_Y_F16, wsg, wsb, sptr)
+
+        for s in range(3):
+            gemm_mfma(s)
+        a.record(stream)
+        for s in range(20):
+            gemm_mfma(s)
+        e.record(stream)
+        torch.cuda.synchronize()
+        us_mfma = a.elapsed_time(e) * 1e3 / 20
+        batch_sweep.append({"batch": b, "lut_us": round(us, 2), "lut_us_per_vector": round(us / b, 2),
+                            "mfma_us": round(us_mfma, 2), "mfma_us_per_vector": round(us_mfma / b, 2)})
         del xb, yb, wsg
 
     out = {

@@ -167,6 +167,18 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
                  int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Same arguments, same result (to the same tolerance) as lutgemm_gemm, computed without
+   tables of partial sums: every key byte is expanded to eight values of +-1 and each
+   plane's B_i . X runs on the matrix cores, fp32 accumulation, one multiplication by the
+   scale per group (section 3.2: y = sum_i A_i o (B_i . x); offset term of eq. 3).  Its
+   time does not grow with batch up to 16 vectors, where the lookup path's does (the
+   limitation discussed in section 6), so it is the faster of the two from a batch of
+   about three.  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
+   included when n % 64 == 0): LUTGEMM_EUNSUPPORTED otherwise.  Bitwise reproducible.     */
+int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                      int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Human-readable name of an error code (static storage).                                */
 const char* lutgemm_strerror(int code);
 

@@ -60,6 +60,8 @@ struct GemvParams {
   int n;                  // columns
   int64_t vec_stride;     // floats between the partials of the two vectors of a pair
   float* spare;           // [256 workgroup slots][16 wavefronts][2][16]: where results nobody reads are stored
+  // matrix-core kernel only
+  int batch;              // activation vectors
 };
 
 // DPP controls (GFX9 encoding)
@@ -862,6 +864,8 @@ __global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
   finish_row_range<2>(p, lut, rs, rb0, rb1);
 }
 
+#include "lutgemm_planes_mfma.h"
+
 // Zero the arrival counters of a fresh workspace.
 __global__ __launch_bounds__(256) void lutgemm_zero_counters_kernel(uint32_t* counters, int count) {
   const int i = blockIdx.x * 256 + threadIdx.x;
@@ -1023,6 +1027,59 @@ void plan_grid(int cus, bool pair, const char* tpg_var, const char* rs_var, Gemv
 constexpr size_t kCounterBytes = 32768;   // 32 activation vectors x 256 row ranges
 constexpr size_t kSpareBytes = 256 * 16 * 32 * sizeof(float);   // 128 bytes per (workgroup slot, wavefront)
 
+
+template <bool HAS_Z, int NB>
+GemvKernel pick_planes_q(int q) {
+#ifdef LUT_ONLY_Q
+  return q == LUT_ONLY_Q ? lutgemm_planes_mfma_kernel<LUT_ONLY_Q, HAS_Z, NB> : nullptr;
+#else
+  switch (q) {
+    case 1: return lutgemm_planes_mfma_kernel<1, HAS_Z, NB>;
+    case 2: return lutgemm_planes_mfma_kernel<2, HAS_Z, NB>;
+    case 3: return lutgemm_planes_mfma_kernel<3, HAS_Z, NB>;
+    case 4: return lutgemm_planes_mfma_kernel<4, HAS_Z, NB>;
+    case 5: return lutgemm_planes_mfma_kernel<5, HAS_Z, NB>;
+    case 6: return lutgemm_planes_mfma_kernel<6, HAS_Z, NB>;
+    case 7: return lutgemm_planes_mfma_kernel<7, HAS_Z, NB>;
+    case 8: return lutgemm_planes_mfma_kernel<8, HAS_Z, NB>;
+  }
+  return nullptr;
+#endif
+}
+
+GemvKernel pick_planes_kernel(int q, bool has_z, int batch) {
+  if (batch <= 16) return has_z ? pick_planes_q<true, 1>(q) : pick_planes_q<false, 1>(q);
+  return has_z ? pick_planes_q<true, 2>(q) : pick_planes_q<false, 2>(q);
+}
+
+// Grid of the matrix-core kernel: K groups x row ranges.  A wavefront keeps the outputs of at
+// most kPlanesMaxUnits row blocks in registers, which bounds the row range; few K groups keep
+// the split-K partials (batch x rows x 4 bytes per group, written and read back) small
+// against the weights.  Costs in microseconds, from measurement on the FC1 shape.
+void plan_planes_grid(int cus, int waves, int batch, GemvParams* p) {
+  const int slots = cus > 256 ? 256 : cus;
+  const int min_rs = (p->RB + kPlanesMaxUnits * waves - 1) / (kPlanesMaxUnits * waves);
+  double best = 1e30;
+  for (int tpg = 1; tpg <= p->NT; ++tpg) {
+    const int kg = (p->NT + tpg - 1) / tpg;
+    if (kg > 256) continue;
+    int rs = slots / kg;
+    rs = rs < min_rs ? min_rs : rs;
+    rs = rs > p->RB ? p->RB : rs;
+    const int blocks = (p->RB + rs - 1) / rs;
+    const int units = (blocks + waves - 1) / waves;
+    const int rounds = (kg * rs + slots - 1) / slots;           // passes of workgroups over the device
+    const double partial_mb = kg > 1 ? (double)kg * p->RB * 16 * batch * 8 / 1e6 : 0.0;
+    const double cost = rounds * (tpg * (units * 2.7 + 1.5)) + partial_mb / 5.0 + (kg > 1 ? 3.0 : 0.0);
+    if (cost < best) {
+      best = cost;
+      p->KG = kg;
+      p->TPG = tpg;
+      p->row_splits = rs;
+    }
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -1106,6 +1163,68 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
       return LUTGEMM_EHIP;
     b += pair ? 2 : 1;
   }
+  return LUTGEMM_OK;
+}
+
+int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                      int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!x || !bits || !alpha || !y || !workspace) return LUTGEMM_EINVAL;
+  if (m < 1 || n < 8 || n % 8 != 0 || q < 1 || q > 8 || g < 0 || batch < 1) return LUTGEMM_EINVAL;
+  const int64_t gg = g == 0 ? n : g;
+  if (gg % 8 != 0 || n % gg != 0) return LUTGEMM_EINVAL;
+  if (!aligned16(x) || !aligned16(bits) || !aligned16(alpha) || !aligned16(z) || !aligned16(y) || !aligned16(workspace))
+    return LUTGEMM_EINVAL;
+  if (mu != 8 || batch > 32 || (flags & ~1u) != 0) return LUTGEMM_EUNSUPPORTED;
+  if (gg % 64 != 0) return LUTGEMM_EUNSUPPORTED;   // a matrix-core step covers 64 columns of one group
+  if (m > (int64_t)1 << 30 || n > (int64_t)1 << 30) return LUTGEMM_EUNSUPPORTED;
+  const size_t need = lutgemm_workspace_bytes(m, n, q, g, mu, batch);
+  if (need == 0) return LUTGEMM_EINVAL;
+  if (workspace_bytes < need) return LUTGEMM_EWORKSPACE;
+
+  const int cus = compute_units();
+  if (cus <= 0) return LUTGEMM_EHIP;
+  GemvParams p;
+  p.x = static_cast<const __half*>(x);
+  p.bits = static_cast<const uint8_t*>(bits);
+  p.alpha = static_cast<const __half*>(alpha);
+  p.z = static_cast<const __half*>(z);
+  p.y = y;
+  p.m = (int)m;
+  p.n = (int)n;
+  p.batch = batch;
+  p.RB = (int)((m + 15) / 16);
+  p.nchunks = (int)(n / 8);
+  p.NT = (p.nchunks + 127) / 128;
+  p.NG = (int)(n / gg);
+  p.g = (int)gg;
+  p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
+  const int waves = q > 4 ? 4 : 8;
+  plan_planes_grid(cus, waves, batch, &p);
+  {
+    const int tpg = env_int("LUTGEMM_MFMA_TPG");
+    if (tpg > 0) {
+      const int min_rs = (p.RB + kPlanesMaxUnits * waves - 1) / (kPlanesMaxUnits * waves);
+      p.TPG = tpg > p.NT ? p.NT : tpg;
+      p.KG = (p.NT + p.TPG - 1) / p.TPG;
+      int rs = (cus > 256 ? 256 : cus) / p.KG;
+      rs = rs < min_rs ? min_rs : rs;
+      p.row_splits = rs > p.RB ? p.RB : rs;
+    }
+  }
+  if (p.row_splits > 256 && p.KG > 1) return LUTGEMM_EUNSUPPORTED;   // 256 arrival counters per call
+  const int64_t m_pad = (int64_t)p.RB * 16;
+  p.kg_stride = m_pad * batch;
+  p.vec_stride = m_pad;
+  p.counters = static_cast<uint32_t*>(workspace);
+  p.spare = nullptr;
+  p.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
+  GemvKernel kern = pick_planes_kernel(q, z != nullptr, batch);
+  if (!kern) return LUTGEMM_EUNSUPPORTED;
+  void* args[] = {&p};
+  if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.KG * p.row_splits), dim3(waves * 64), args, 0,
+                      static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return LUTGEMM_EHIP;
   return LUTGEMM_OK;
 }
 

@@ -1,0 +1,426 @@
+// Plane-wise matrix-core path for small batches — included inside the anonymous namespace of
+// lutgemm_device.hip (it uses GemvParams and the helpers defined there).
+//
+// Same result as the lookup path, y = sum_i A_i o (B_i . X) (section 3.2, eq. 3), but the
+// binary planes go through the matrix cores instead of through tables of partial sums: every
+// key byte is expanded to eight fp16 values of +-1 (two reads of a 16-entry table in LDS),
+// B_i . X is accumulated per group on v_mfma_f32_16x16x32_f16 (products +-x are exact, the
+// accumulation is fp32), and the group's scale multiplies the accumulator once per group
+// (section 3.2 rule 2).  This is the alternative the paper's discussion of batch points to
+// (section 6: with growing batch the table lookups become the limit): its cost does not grow
+// with batch up to 16 vectors, so it overtakes the lookup path at a batch of about three.
+//
+// Work split: a workgroup owns a row range and a K group (a run of K tiles) and keeps the
+// outputs of its row blocks in registers across the tiles of the group; K groups are combined
+// as in the GEMV kernel (partials, arrival counter, last workgroup sums in group order), or
+// not at all when there is one K group.  Group size must be a multiple of 64 columns.
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int Q>
+struct PlanesCfg {
+  static constexpr int kWavesM = Q > 4 ? 4 : 8;         // wavefronts per workgroup
+  static constexpr int kThreadsM = kWavesM * 64;
+  static constexpr int kMaxSeg = 17;                    // group segments a tile can touch (g >= 64)
+  static constexpr int kStageBytes = Q * 2048;          // per wavefront: Q planes x 2 sub-slabs, regrouped
+  static constexpr int kAlphaBytes = kMaxSeg * Q * 32;  // per wavefront: scales of one unit
+  static constexpr int kZBytes = kMaxSeg * 32;          // per wavefront: offsets of one unit
+  static constexpr int kAlphaPasses = (kAlphaBytes + 1023) / 1024;
+};
+constexpr int kPlanesMaxUnits = 3;   // row blocks per wavefront (outputs held in registers)
+
+// LDS map (bytes): sign table | block sums | X tile | per-wavefront key / scale / offset staging
+constexpr int kSignOff = 0;          // 16 nibbles x 32 copies x 8 B
+constexpr int kBlkSumOff = 4096;     // 16 blocks x 32 vectors fp32
+constexpr int kXOff = 6144;          // 128 chunks x (NB * 16) vectors x 16 B
+
+template <int Q, int NB>
+constexpr int planes_lds_bytes() {
+  using C = PlanesCfg<Q>;
+  return kXOff + 32768 * NB + C::kWavesM * (C::kStageBytes + C::kAlphaBytes + C::kZBytes);
+}
+
+// Raw data of one unit (K tile x row block) as fetched from memory, before it is regrouped in LDS.
+template <int Q, bool HAS_Z>
+struct PlanesRaw {
+  u32x4 w[Q][2];
+  u32x4 al[PlanesCfg<Q>::kAlphaPasses];
+  u32x4 zz;
+};
+
+struct PlanesTile {
+  int kt, chunks, T, nblk, G0, nseg;
+  int64_t base;
+};
+
+__device__ __forceinline__ PlanesTile planes_tile_info(const GemvParams& p, int kt, int Q) {
+  PlanesTile t;
+  t.kt = kt;
+  t.chunks = min(128, p.nchunks - 128 * kt);
+  t.T = t.chunks > 64 ? 2 : 1;
+  t.nblk = t.chunks / (4 * t.T);                         // blocks of 4 slots (32 * T columns)
+  t.G0 = (1024 * kt) / p.g;
+  t.nseg = (1024 * kt + t.chunks * 8 - 1) / p.g - t.G0 + 1;
+  t.base = (int64_t)kt * p.RB * Q * 2048;
+  return t;
+}
+
+template <int Q, bool HAS_Z>
+__device__ __forceinline__ void planes_fetch(PlanesRaw<Q, HAS_Z>& r, const GemvParams& p, const PlanesTile& t, int rb,
+                                             int lane) {
+  using C = PlanesCfg<Q>;
+  const u32x4* bp = reinterpret_cast<const u32x4*>(p.bits + t.base + (int64_t)rb * Q * t.T * 1024) + lane;
+#pragma unroll
+  for (int i = 0; i < Q; ++i) {
+    r.w[i][0] = __builtin_nontemporal_load(bp + (i * t.T) * 64);
+    if (t.T == 2) r.w[i][1] = __builtin_nontemporal_load(bp + (i * 2 + 1) * 64);
+  }
+  // the unit's scales are one contiguous block: [segment][quarter][plane][4 rows] fp16
+  const unsigned char* ap = reinterpret_cast<const unsigned char*>(p.alpha + ((int64_t)rb * p.NG + t.G0) * 16 * Q);
+  const int abytes = t.nseg * Q * 32;
+#pragma unroll
+  for (int k = 0; k < C::kAlphaPasses; ++k) {
+    const int off = (k * 64 + lane) * 16;
+    if (off < abytes) r.al[k] = *reinterpret_cast<const u32x4*>(ap + off);
+  }
+  if (HAS_Z) {
+    const unsigned char* zp = reinterpret_cast<const unsigned char*>(p.z + ((int64_t)rb * p.NG + t.G0) * 16);
+    if (lane * 16 < t.nseg * 32) r.zz = *reinterpret_cast<const u32x4*>(zp + lane * 16);
+  }
+}
+
+// Regroup a fetched unit in this wavefront's LDS staging area.  Key words: lane 4j + k holds,
+// in dword s, rows 4k..4k+3 of slot 4j + (s + k) % 4; they are stored as [plane][sub-slab]
+// [block j][slot in block][quarter k], so that the 16 dwords a matrix-core step needs are
+// consecutive.
+template <int Q, bool HAS_Z>
+__device__ __forceinline__ void planes_stage(const PlanesRaw<Q, HAS_Z>& r, const PlanesTile& t, int lane,
+                                             uint32_t* stage, unsigned char* astage, unsigned char* zstage) {
+  using C = PlanesCfg<Q>;
+  const int j = lane >> 2, k = lane & 3;
+#pragma unroll
+  for (int i = 0; i < Q; ++i)
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      if (tt < t.T) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          stage[i * 512 + (tt * 16 + j) * 16 + ((s + k) & 3) * 4 + k] = r.w[i][tt][s];
+      }
+    }
+  const int abytes = t.nseg * Q * 32;
+#pragma unroll
+  for (int kk = 0; kk < C::kAlphaPasses; ++kk) {
+    const int off = (kk * 64 + lane) * 16;
+    if (off < abytes) *reinterpret_cast<u32x4*>(astage + off) = r.al[kk];
+  }
+  if (HAS_Z && lane * 16 < t.nseg * 32) *reinterpret_cast<u32x4*>(zstage + lane * 16) = r.zz;
+}
+
+// One unit: all planes, all blocks of the tile; fin[nb][r] += contribution of this tile to
+// row 4 * (lane / 16) + r of the block for activation vector nb * 16 + lane % 16.
+// The key words of four blocks are read from the staging area in one go; then, block by
+// block: key byte -> two sign-table reads -> matrix-core instructions, fully unrolled.  The
+// scales of a group are read when the group starts and used when it ends.  (The path is
+// bound by LDS bandwidth: 16 bytes of +-1 values per lane and matrix-core instruction.)
+template <int Q, int NB, int T>
+struct PlanesOperands {
+  f16x8 a[T][Q];    // +-1 rows of the planes
+  f16x8 b[T][NB];   // activations
+};
+
+template <int Q, int NB, int T>
+__device__ __forceinline__ void planes_issue(PlanesOperands<Q, NB, T>& o, const uint32_t (&kd)[Q][T][4], int jj, int j,
+                                             int key_shift, const u32x2* my_sign, const f16x8* my_x) {
+  constexpr int NB16 = NB * 16;
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) o.b[tt][nb] = my_x[(T * 4 * j + tt) * NB16 + nb * 16];
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+      // two 8-byte reads (low and high nibble of the key), each from this lane's own copy of
+      // the 16-entry table: no two lanes of a pass share a bank
+      const uint32_t key = kd[i][tt][jj] >> key_shift;
+      const u32x2 lo = my_sign[(key & 15u) * 32];
+      const u32x2 hi = my_sign[((key >> 4) & 15u) * 32];
+      o.a[tt][i] = __builtin_bit_cast(f16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
+    }
+  }
+}
+
+template <int Q, bool HAS_Z, int NB, int T>
+__device__ __forceinline__ void planes_compute(const GemvParams& p, const PlanesTile& t, int lane, const u32x2* sign,
+                                               const float* blksum, const f16x8* Xs, const uint32_t* stage,
+                                               const unsigned char* astage, const unsigned char* zstage,
+                                               f32x4 (&fin)[NB]) {
+  constexpr int NB16 = NB * 16;
+  const int sub = lane >> 4;        // slot within the block / quarter of the output rows
+  const int col = lane & 15;        // row supplied to the A operand / activation vector of the outputs
+  const int key_shift = 8 * (col & 3);
+  f32x4 acc[Q][NB];
+  float sx[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    sx[nb] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < Q; ++i) acc[i][nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  }
+  constexpr int cols_per_blk = 32 * T;
+  const uint32_t* my_stage = stage + sub * 4 + (col >> 2);
+  const u32x2* my_sign = sign + (lane & 31);
+  const f16x8* my_x = Xs + (T * sub) * NB16 + col;
+  const unsigned char* my_alpha = astage + sub * Q * 8;
+  const unsigned char* my_z = zstage + sub * 8;
+  int seg = 0;                      // group segment of the current block, relative to t.G0
+  u32x2 a4[Q], z4;                  // scales / offsets of segment `seg` for this lane's four rows
+#pragma unroll
+  for (int i = 0; i < Q; ++i) a4[i] = *reinterpret_cast<const u32x2*>(my_alpha + i * 8);
+  if (HAS_Z) z4 = *reinterpret_cast<const u32x2*>(my_z);
+
+#pragma unroll 1
+  for (int j0 = 0; j0 < t.nblk; j0 += 4) {
+    uint32_t kd[Q][T][4];
+#pragma unroll
+    for (int i = 0; i < Q; ++i)
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) kd[i][tt][jj] = my_stage[i * 512 + (tt * 16 + j0 + jj) * 16];
+    // Operands of the next block are read while the current block is on the matrix cores,
+    // where two sets of operands fit the registers (few planes); otherwise block by block.
+    constexpr bool kAhead = Q * NB <= 3;
+    PlanesOperands<Q, NB, T> ops[kAhead ? 2 : 1];
+    if (kAhead) planes_issue<Q, NB, T>(ops[0], kd, 0, j0, key_shift, my_sign, my_x);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + jj;
+      // (blocks past the end of a ragged tile read stale but valid staging memory and are not used)
+      if (kAhead) {
+        if (jj < 3) planes_issue<Q, NB, T>(ops[(jj + 1) & 1], kd, jj + 1, j + 1, key_shift, my_sign, my_x);
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+        planes_issue<Q, NB, T>(ops[0], kd, jj, j, key_shift, my_sign, my_x);
+      }
+      if (j < t.nblk) {   // wave-uniform
+        const PlanesOperands<Q, NB, T>& o = ops[kAhead ? (jj & 1) : 0];
+#pragma unroll
+        for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+          for (int i = 0; i < Q; ++i)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(o.a[tt][i], o.b[tt][nb], acc[i][nb], 0, 0, 0);
+        if (HAS_Z) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) sx[nb] += blksum[j * 32 + nb * 16 + col];
+        }
+        const int next_seg = (1024 * t.kt + (j + 1) * cols_per_blk) / p.g - t.G0;
+        if (j == t.nblk - 1 || next_seg != seg) {   // wave-uniform: the group ends here (section 3.2 rule 2)
+#pragma unroll
+          for (int i = 0; i < Q; ++i) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float af = half_of(a4[i], r);
+#pragma unroll
+              for (int nb = 0; nb < NB; ++nb) fin[nb][r] = fmaf(af, acc[i][nb][r], fin[nb][r]);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+          }
+          if (HAS_Z) {   // offset term of eq. 3
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float zf = half_of(z4, r);
+#pragma unroll
+              for (int nb = 0; nb < NB; ++nb) fin[nb][r] = fmaf(zf, sx[nb], fin[nb][r]);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) sx[nb] = 0.0f;
+          }
+          seg = min(next_seg, t.nseg - 1);   // the next group's scales, used when that group ends
+#pragma unroll
+          for (int i = 0; i < Q; ++i) a4[i] = *reinterpret_cast<const u32x2*>(my_alpha + (seg * 4 * Q + i) * 8);
+          if (HAS_Z) z4 = *reinterpret_cast<const u32x2*>(my_z + seg * 32);
+        }
+      }
+    }
+  }
+}
+
+// Sum of the K groups by the last workgroup to arrive for a row range, all activation vectors
+// (the GEMV kernel's final reduction with a run-time vector count and workgroup size).
+template <int THREADS>
+__device__ __forceinline__ void finish_rows_batch(const GemvParams& p, uint32_t* flag, int rs, int rb0, int rb1) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t arrived = __hip_atomic_fetch_add(p.counters + rs, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    flag[0] = (arrived == (uint32_t)(p.KG - 1)) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (flag[0] == 0u) return;
+  constexpr int kRows = 4;
+  const int row_end = min(rb1 * 16, p.m);
+  for (int vec = 0; vec < p.batch; ++vec) {
+    const float* part = p.partial + (int64_t)vec * p.vec_stride;
+    for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRows * THREADS) {
+      float sum[kRows];
+#pragma unroll
+      for (int j = 0; j < kRows; ++j) sum[j] = 0.0f;
+      for (int kb = 0; kb < p.KG; kb += 8) {
+        float v[kRows][8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
+#pragma unroll
+          for (int j = 0; j < kRows; ++j) v[j][u] = load_device_coherent(part + min(r0 + j * THREADS, row_end - 1) + off);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const bool live = kb + u < p.KG;
+#pragma unroll
+          for (int j = 0; j < kRows; ++j) sum[j] += live ? v[j][u] : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kRows; ++j) {
+        const int r = r0 + j * THREADS;
+        if (r < row_end) {
+          if (p.y_f32)
+            static_cast<float*>(p.y)[(int64_t)vec * p.m + r] = sum[j];
+          else
+            static_cast<__half*>(p.y)[(int64_t)vec * p.m + r] = __float2half_rn(sum[j]);
+        }
+      }
+    }
+  }
+  if (threadIdx.x == 0) __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int Q, bool HAS_Z, int NB>
+__global__ __launch_bounds__(PlanesCfg<Q>::kThreadsM) void lutgemm_planes_mfma_kernel(GemvParams p) {
+  using C = PlanesCfg<Q>;
+  constexpr int NB16 = NB * 16;
+  constexpr int kThr = C::kThreadsM;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[planes_lds_bytes<Q, NB>()];
+  u32x2* sign = reinterpret_cast<u32x2*>(lds + kSignOff);
+  float* blksum = reinterpret_cast<float*>(lds + kBlkSumOff);
+  u32x4* Xs = reinterpret_cast<u32x4*>(lds + kXOff);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  unsigned char* wave_area = lds + kXOff + 32768 * NB + wave * (C::kStageBytes + C::kAlphaBytes + C::kZBytes);
+  uint32_t* stage = reinterpret_cast<uint32_t*>(wave_area);
+  unsigned char* astage = wave_area + C::kStageBytes;
+  unsigned char* zstage = astage + C::kAlphaBytes;
+
+  // nibble -> four fp16 values of +-1 (bit j set: +1), 32 copies side by side (one per lane of
+  // an 8-byte read pass): entry (nibble, copy) at nibble * 256 + copy * 8 bytes
+  for (int k = threadIdx.x; k < 512; k += kThr) {
+    const int nib = k >> 5;
+    const uint32_t one = 0x3C00u, minus_one = 0xBC00u;
+    u32x2 e;
+    e.x = ((nib & 1) ? one : minus_one) | (((nib & 2) ? one : minus_one) << 16);
+    e.y = ((nib & 4) ? one : minus_one) | (((nib & 8) ? one : minus_one) << 16);
+    sign[k] = e;
+  }
+
+  const int kg = blockIdx.x % p.KG;
+  const int rs = blockIdx.x / p.KG;
+  const int rb0 = (int)((int64_t)p.RB * rs / p.row_splits);
+  const int rb1 = (int)((int64_t)p.RB * (rs + 1) / p.row_splits);
+  const int kt0 = kg * p.TPG;
+  const int kt1 = min(kt0 + p.TPG, p.NT);
+
+  // this wavefront's row blocks: rb0 + wave + u * waves, u < kPlanesMaxUnits (the host sizes
+  // the row ranges accordingly)
+  f32x4 fin[kPlanesMaxUnits][NB];
+#pragma unroll
+  for (int u = 0; u < kPlanesMaxUnits; ++u)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) fin[u][nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+  PlanesRaw<Q, HAS_Z> raw;
+  if (kt0 < kt1 && rb0 + wave < rb1) {
+    const PlanesTile t0 = planes_tile_info(p, kt0, Q);
+    planes_fetch(raw, p, t0, rb0 + wave, lane);
+  }
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const PlanesTile t = planes_tile_info(p, kt, Q);
+    __syncthreads();   // the previous tile's X is no longer read (first pass: nothing to wait for)
+    for (int idx = threadIdx.x; idx < 128 * NB16; idx += kThr) {
+      const int c = idx / NB16, n = idx % NB16;
+      u32x4 v = u32x4{0u, 0u, 0u, 0u};
+      if (c < t.chunks && n < p.batch)
+        v = *reinterpret_cast<const u32x4*>(p.x + (int64_t)n * p.n + (int64_t)(128 * kt + c) * 8);
+      Xs[idx] = v;
+    }
+    __syncthreads();
+    if (HAS_Z) {   // sum of the activations of every block (the offset term needs it per group)
+      for (int idx = threadIdx.x; idx < 16 * NB16; idx += kThr) {
+        const int j = idx / NB16, n = idx % NB16;
+        float s = 0.0f;
+        for (int c = 4 * t.T * j; c < 4 * t.T * (j + 1); ++c) {
+          const u32x4 v = Xs[c * NB16 + n];
+          s += (half_lo(v.x) + half_hi(v.x)) + (half_lo(v.y) + half_hi(v.y)) + (half_lo(v.z) + half_hi(v.z)) +
+               (half_lo(v.w) + half_hi(v.w));
+        }
+        blksum[j * 32 + n] = s;
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < kPlanesMaxUnits; ++u) {
+      const int rb = rb0 + wave + u * C::kWavesM;
+      if (rb < rb1) {   // wave-uniform
+        planes_stage(raw, t, lane, stage, astage, zstage);
+        // fetch the next unit of this wavefront (same tile, else first row block of the next tile)
+        const int rb_next = rb + C::kWavesM;
+        if (u + 1 < kPlanesMaxUnits && rb_next < rb1) {
+          planes_fetch(raw, p, t, rb_next, lane);
+        } else if (kt + 1 < kt1) {
+          const PlanesTile tn = planes_tile_info(p, kt + 1, Q);
+          planes_fetch(raw, p, tn, rb0 + wave, lane);
+        }
+        if (t.T == 2)
+          planes_compute<Q, HAS_Z, NB, 2>(p, t, lane, sign, blksum, reinterpret_cast<const f16x8*>(Xs), stage, astage,
+                                          zstage, fin[u]);
+        else
+          planes_compute<Q, HAS_Z, NB, 1>(p, t, lane, sign, blksum, reinterpret_cast<const f16x8*>(Xs), stage, astage,
+                                          zstage, fin[u]);
+      }
+    }
+  }
+
+  // ---- outputs: row 4 * (lane / 16) + r of block rb, activation vector nb * 16 + lane % 16 ----
+  const int sub = lane >> 4, col = lane & 15;
+#pragma unroll
+  for (int u = 0; u < kPlanesMaxUnits; ++u) {
+    const int rb = rb0 + wave + u * C::kWavesM;
+    if (rb < rb1) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int vec = nb * 16 + col;
+        if (vec < p.batch) {
+          const int row = rb * 16 + 4 * sub;
+          if (p.KG == 1) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              if (row + r < p.m) {
+                if (p.y_f32)
+                  static_cast<float*>(p.y)[(int64_t)vec * p.m + row + r] = fin[u][nb][r];
+                else   // fp16 output, nearest even (paper table 1)
+                  static_cast<__half*>(p.y)[(int64_t)vec * p.m + row + r] = __float2half_rn(fin[u][nb][r]);
+              }
+            }
+          } else {
+            float* dst = p.partial + (int64_t)kg * p.kg_stride + (int64_t)vec * p.vec_stride + row;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) store_device_coherent(dst + r, fin[u][nb][r]);
+          }
+        }
+      }
+    }
+  }
+  if (p.KG > 1) finish_rows_batch<kThr>(p, reinterpret_cast<uint32_t*>(lds), rs, rb0, rb1);
+}

@@ -41,8 +41,8 @@ def make_workspace(nbytes, stream=None):
     return d_ws
 
 
-def run(packed, x16, f32_out=False, stream=None, workspace=None):
-    """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x) for the packed layer.
+def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False):
+    """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x; lutgemm_gemm_mfma if mfma) for the packed layer.
     y is pre-filled with NaN: it must be fully overwritten, never read."""
     torch = torch_cuda()
     p = packed
@@ -57,7 +57,10 @@ def run(packed, x16, f32_out=False, stream=None, workspace=None):
     s = torch.cuda.current_stream() if stream is None else stream
     flags = L.LUTGEMM_Y_F32 if f32_out else L.LUTGEMM_Y_F16
     torch.cuda.synchronize()
-    if x16.ndim == 1:
+    if mfma:
+        L.lutgemm_gemm_mfma(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
+                            d_ws.numel(), s.cuda_stream)
+    elif x16.ndim == 1:
         L.lutgemm_gemv(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, flags, d_ws, d_ws.numel(),
                        s.cuda_stream)
     else:

@@ -135,6 +135,10 @@ def test_argument_validation_returns_codes_without_gpu():
     assert gemv(wsb=16) == L.LUTGEMM_EWORKSPACE
     assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 33, 0, p16, 1 << 20, None) == L.LUTGEMM_EUNSUPPORTED
     assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 0, 0, p16, 1 << 20, None) == L.LUTGEMM_EINVAL
+    assert lib.lutgemm_gemm_mfma(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 33, 0, p16, 1 << 20, None) == L.LUTGEMM_EUNSUPPORTED
+    assert lib.lutgemm_gemm_mfma(p16, p16, p16, None, p16, 3, 32, 8, 16, 64, 2, 0, p16, 1 << 20, None) == L.LUTGEMM_EUNSUPPORTED
+    assert lib.lutgemm_gemm_mfma(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 0, 0, p16, 1 << 20, None) == L.LUTGEMM_EINVAL
+    assert lib.lutgemm_gemm_mfma(None, p16, p16, None, p16, 3, 64, 8, 16, 64, 2, 0, p16, 1 << 20, None) == L.LUTGEMM_EINVAL
     assert lib.lutgemm_workspace_init(None, 1 << 20, None) == L.LUTGEMM_EINVAL
     assert lib.lutgemm_workspace_init(p16, 1024, None) == L.LUTGEMM_EWORKSPACE
     assert lib.lutgemm_strerror(L.LUTGEMM_EWORKSPACE) == b"workspace too small"

@@ -113,3 +113,40 @@ def test_small_batch_on_fc1_shape():
     Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g, rows=rows)
     for b in range(3):
         check_parity(Y[b][rows], Yref[b], X[b], bound[rows], f32_out=True)
+
+
+@pytest.mark.parametrize("batch", [4, 32])
+def test_mfma_path_on_fc1_shape(batch):
+    # config 5 through the matrix-core path, in the launch configuration bench.py times
+    m, n = synth.OPT_175B["fc1"]
+    q, g = 3, 128
+    print(f"case mfma fc1 m={m} n={n} batch={batch}", flush=True)
+    W = synth.weights_fp16(m, n, seed=5000)
+    p = Packed.from_weights(W, q, g)
+    del W
+    X = synth.activations_fp16(n, seed=5600 + batch, batch=batch)
+    Y = run(p, X, f32_out=True, mfma=True)
+    rows = _sample_rows(m, np.random.default_rng(6))
+    a = O.decode_alpha(p.alpha, m, n // g, q)
+    bound = row_l1_bound(a, None, g)
+    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g, rows=rows)
+    for b in range(batch):
+        check_parity(Y[b][rows], Yref[b], X[b], bound[rows], f32_out=True)
+
+
+def test_mfma_path_llama65b_down_with_offset():
+    m, n = synth.LLAMA_65B["down"]
+    q, g = 4, 128
+    print(f"case mfma llama down m={m} n={n}", flush=True)
+    W = synth.weights_fp16(m, n, seed=5700)
+    p = Packed.from_weights(W, q, g, L.LUTGEMM_Q_UNIFORM_RTN)
+    del W
+    X = synth.activations_fp16(n, seed=5701, batch=8)
+    Y = run(p, X, f32_out=True, mfma=True)
+    rows = _sample_rows(m, np.random.default_rng(7))
+    a = O.decode_alpha(p.alpha, m, n // g, q)
+    z = O.decode_z(p.z, m, n // g)
+    bound = row_l1_bound(a, z, g)
+    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, p.z, X, m, n, q, g, rows=rows)
+    for b in range(8):
+        check_parity(Y[b][rows], Yref[b], X[b], bound[rows], f32_out=True)

@@ -147,3 +147,45 @@ def test_runs_on_a_side_stream():
     s = torch.cuda.Stream()
     y_side = run(p, x, f32_out=True, stream=s)
     np.testing.assert_array_equal(y_side, run(p, x, f32_out=True))
+
+
+# ---- matrix-core path (lutgemm_gemm_mfma): same oracle, same tolerances ----
+
+MFMA_CASES = [
+    (1024, 1024, 3, 128, "greedy", 4),
+    (333, 2048, 3, 128, "greedy_z", 5),     # ragged rows, offsets
+    (1000, 1536, 4, 128, "greedy_z", 16),   # last tile with exactly 64 chunks (one sub-slab)
+    (77, 576, 3, 0, "greedy", 1),           # single ragged tile, row-wise scales, one vector
+    (300, 2048, 2, 64, "rtn", 17),          # smallest supported group, more than 16 vectors
+    (4100, 3072, 3, 128, "greedy", 32),     # several workgroups, ragged split of row blocks, full batch
+    (515, 5120, 4, 128, "greedy", 2),
+    (130, 4224, 5, 192, "greedy_z", 3),     # q > 4 (4-wavefront workgroups), groups that straddle K tiles
+    (96, 1088, 8, 64, "rtn", 20),           # eight planes, ragged last tile of 8 chunks
+    (16, 64, 1, 64, "greedy", 32),          # smallest supported problem
+]
+
+
+@pytest.mark.parametrize("m,n,q,g,mode,batch", MFMA_CASES)
+def test_mfma_path_matches_oracle(m, n, q, g, mode, batch):
+    print(f"case mfma m={m} n={n} q={q} g={g} mode={mode} batch={batch}", flush=True)
+    W = synth.weights_fp16(m, n, seed=6000 + m + 7 * n + q)
+    X = synth.activations_fp16(n, seed=6500 + m + n, batch=batch)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    bound = _bound(p)
+    Y32 = run(p, X, f32_out=True, mfma=True)
+    assert Y32.shape == (batch, m)
+    for b in range(batch):
+        check_parity(Y32[b], _oracle_full(p, X[b]), X[b], bound, f32_out=True)
+    Y16 = run(p, X, mfma=True)
+    np.testing.assert_array_equal(Y32.astype(np.float16), Y16)
+    np.testing.assert_array_equal(run(p, X, f32_out=True, mfma=True), Y32)   # bitwise reproducible
+
+
+def test_mfma_path_rejects_groups_not_multiple_of_64():
+    m, n, q, g = 64, 1024, 2, 32
+    W = synth.weights_fp16(m, n, seed=6900)
+    p = Packed.from_weights(W, q, g)
+    X = synth.activations_fp16(n, seed=6901, batch=2)
+    with pytest.raises(L.LutGemmError) as e:
+        run(p, X, mfma=True)
+    assert e.value.code == L.LUTGEMM_EUNSUPPORTED
