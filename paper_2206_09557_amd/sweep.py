@@ -1,0 +1,76 @@
+"""Latency against footprint over (q, g) at one layer shape (paper section 3.4, figure 4b:
+batch-1 latency follows the memory footprint of eq. 4, and a small group size raises it).
+
+    python -m paper_2206_09557_amd.sweep [--m 12288 --n 12288 --iters 50]
+
+The kernel is data-oblivious, so the packed buffers are filled with random key bytes and
+random positive fp16 scales directly on the device (no quantiser run): sizes, layouts and
+access pattern are those of a packed layer.  Several copies of every configuration rotate so
+that the 256 MB Infinity Cache does not serve the weights.  Prints a markdown table.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--m", type=int, default=12288)
+    ap.add_argument("--n", type=int, default=12288)
+    ap.add_argument("--iters", type=int, default=50)
+    ap.add_argument("--q", type=str, default="1,2,3,4,5,6,7,8")
+    ap.add_argument("--g", type=str, default="32,64,128,256,0")
+    args = ap.parse_args(argv)
+
+    import torch
+
+    from . import lutgemm as L
+
+    if not torch.cuda.is_available():
+        print("sweep: no GPU visible", file=sys.stderr)
+        return 2
+    L.lib()
+    m, n = args.m, args.n
+    stream = torch.cuda.current_stream().cuda_stream
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    x = torch.randn(n, device="cuda", generator=gen).half()
+    y = torch.empty(m, dtype=torch.float16, device="cuda")
+    rows = []
+    for q in [int(v) for v in args.q.split(",")]:
+        for g in [int(v) for v in args.g.split(",")]:
+            nb, na = L.lutgemm_bits_bytes(m, n, q), L.lutgemm_alpha_bytes(m, n, q, g)
+            copies = max(2, min(8, int(1.2e9 // (nb + na)) or 2))
+            bits = [torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=gen) for _ in range(copies)]
+            alpha = [(torch.rand(na // 2, device="cuda", generator=gen) * 0.05 + 0.001).half() for _ in range(copies)]
+            wsb = L.lutgemm_workspace_bytes(m, n, q, g)
+            ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+            L.lutgemm_workspace_init(ws, wsb, stream)
+
+            def go(i):
+                L.lutgemm_gemv(x, bits[i % copies], alpha[i % copies], None, y, q, g, 8, m, n, L.LUTGEMM_Y_F16, ws, wsb,
+                               stream)
+
+            for i in range(5):
+                go(i)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for i in range(args.iters):
+                go(i)
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / args.iters
+            gg = n if g == 0 else g
+            footprint = m * n * q // 8 + 2 * m * (n // gg) * q      # eq. 4 in bytes
+            rows.append((q, g, footprint, us))
+            del bits, alpha, ws
+            print(f"[sweep] q={q} g={g or 'row'}: {us:.2f} us", file=sys.stderr, flush=True)
+    print(f"| q | g | footprint MB (eq. 4) | us / GEMV | GB/s | us per MB |")
+    print("|---|---|---|---|---|---|")
+    for q, g, fp, us in rows:
+        print(f"| {q} | {g or 'row'} | {fp / 1e6:.2f} | {us:.2f} | {fp / us / 1e3:.0f} | {us / (fp / 1e6):.3f} |")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
