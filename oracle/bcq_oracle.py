@@ -303,14 +303,45 @@ def decode_z(packed, m, NG):
     return np.ascontiguousarray(a.transpose(0, 2, 1).reshape(RB * 16, NG)[:m, :])
 
 
-def gemv_packed(bits, alpha_p, z_p, x, m, n, q, g, rows=None):
+def share_scales(alpha):
+    """Appendix C gives the planes of a uniformly quantised group the scales
+    alpha_i = 2^i * alpha_0, so one stored value per (row, group) carries them all.
+    alpha fp16-valued [q][m][NG] -> alpha_0 [m][NG]; raises if some alpha_i is not exactly
+    2^i * alpha_0 (the scales of a greedy quantiser are not)."""
+    a = np.asarray(alpha, dtype=np.float64)
+    base = a[0]
+    for i in range(a.shape[0]):
+        if not np.array_equal(a[i], base * 2.0 ** i):
+            raise ValueError("scales are not powers of two times the first plane's")
+    return np.asarray(alpha)[0].astype(np.float16)
+
+
+def expand_shared(alpha0, q):
+    """alpha_0 [m][NG] -> alpha [q][m][NG] with alpha_i = 2^i * alpha_0 (fp64)."""
+    a0 = np.asarray(alpha0, dtype=np.float64)
+    return np.stack([a0 * 2.0 ** i for i in range(q)])
+
+
+def encode_alpha_shared(alpha0):
+    """Shared-scale layout: fp16 [row block][group][16 rows], the layout of the offsets."""
+    return encode_z(alpha0)
+
+
+def decode_alpha_shared(packed, m, NG):
+    return decode_z(packed, m, NG)
+
+
+def gemv_packed(bits, alpha_p, z_p, x, m, n, q, g, rows=None, alpha_shared=False):
     """y (fp64) straight from the packed buffers: decode, then the definition above.
     rows: optional 1-D index array; only those output rows are computed (the rest of the
     matrix is never dequantised), so single outputs of very large layers stay cheap."""
     g = n if g == 0 else g
     NG = n // g
     x = np.asarray(x, dtype=np.float64)
-    alpha = decode_alpha(alpha_p, m, NG, q)
+    if alpha_shared:   # one scale per (row, group); plane i has 2^i times it (appendix C)
+        alpha = expand_shared(decode_alpha_shared(alpha_p, m, NG), q)
+    else:
+        alpha = decode_alpha(alpha_p, m, NG, q)
     z = None if z_p is None else decode_z(z_p, m, NG)
     if rows is None:
         B = decode_bits(bits, m, n, q)

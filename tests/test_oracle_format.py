@@ -125,6 +125,34 @@ def test_uniform_rtn_error_bound_and_degenerate_group():
     assert np.all(B[:, 3, 32:64] == 1) and np.all(alpha[:, 3, 1] == 0) and z[3, 1] == np.float16(0.0123)
 
 
+def test_shared_scales_are_the_appendix_c_scales():
+    # appendix C: alpha_i = 2^i * alpha_0 for a uniformly quantised group, so alpha_0 alone
+    # carries the scales; the shared form gives the same dequantised weights and products
+    rng = np.random.default_rng(16)
+    W = (rng.standard_normal((21, 256)) * 0.02).astype(np.float16)
+    q, g = 4, 64
+    B, alpha, z = O.quantize_uniform_rtn(W, q, g)
+    a0 = O.share_scales(alpha)
+    assert a0.dtype == np.float16 and a0.shape == (21, 4)
+    np.testing.assert_array_equal(O.expand_shared(a0, q), alpha.astype(np.float64))
+    for i in range(q):                                   # closed form of the conversion
+        np.testing.assert_array_equal(alpha[i].astype(np.float64), a0.astype(np.float64) * 2.0 ** i)
+    x = rng.standard_normal(256).astype(np.float16)
+    bits = O.encode_bits(B)
+    y_planes = O.gemv_packed(bits, O.encode_alpha(alpha), O.encode_z(z), x, 21, 256, q, g)
+    y_shared = O.gemv_packed(bits, O.encode_alpha_shared(a0), O.encode_z(z), x, 21, 256, q, g, alpha_shared=True)
+    np.testing.assert_array_equal(y_planes, y_shared)
+    # and against the integer form  w = s * u + zhat  with s = 2 * alpha_0 (dense numpy product)
+    u = sum(((B[i] + 1) // 2).astype(np.int64) << i for i in range(q))
+    s_full = np.repeat(2.0 * a0.astype(np.float64), g, axis=1)
+    zhat = np.repeat(z.astype(np.float64) - a0.astype(np.float64) * (2 ** q - 1), g, axis=1)
+    np.testing.assert_allclose((s_full * u + zhat) @ x.astype(np.float64), y_shared, rtol=1e-12, atol=1e-12)
+    # scales of a greedy quantiser are not of that form
+    _, alpha_g, _ = O.quantize_greedy(W, 3, g)
+    with pytest.raises(ValueError):
+        O.share_scales(alpha_g)
+
+
 # ---- packed layouts: hand-written bytes ------------------------------------------------
 def _load_layout_cases(golden_dir):
     cases, cur, extra = [], None, []
@@ -191,8 +219,16 @@ def test_packed_scale_indices_match_hand_written(golden_dir):
             assert p.size == -(-m // 16) * NG * 16
             assert np.flatnonzero(p).tolist() == [idx]
             np.testing.assert_array_equal(O.decode_z(p, m, NG), z)
+        elif t[0] == "shared":
+            m, NG, r, G, idx = (int(v) for v in t[1:])
+            a0 = np.zeros((m, NG), dtype=np.float16)
+            a0[r, G] = 0.75
+            p = O.encode_alpha_shared(a0)
+            assert p.size == -(-m // 16) * NG * 16
+            assert np.flatnonzero(p).tolist() == [idx]
+            np.testing.assert_array_equal(O.decode_alpha_shared(p, m, NG), a0)
         seen += 1
-    assert seen == 5
+    assert seen == 7
 
 
 @pytest.mark.parametrize("m,n,q", [(1, 8, 1), (17, 520, 3), (33, 1544, 2), (16, 2048, 4), (50, 1024 + 512, 3)])
