@@ -97,7 +97,12 @@ enum {
 /* `flags` of lutgemm_gemv / lutgemm_gemm. */
 enum {
   LUTGEMM_Y_F16 = 0, /* y is fp16, rounded to nearest even from the fp32 sum (paper table 1: FP16 output) */
-  LUTGEMM_Y_F32 = 1  /* y is fp32 */
+  LUTGEMM_Y_F32 = 1, /* y is fp32 */
+  /* `alpha` is in the shared-scale layout: ONE fp16 per (row, group), alpha_0, and plane i
+     has the scale 2^i * alpha_0, as appendix C gives for uniformly quantised weights
+     (buffer of lutgemm_alpha_shared_bytes, written by lutgemm_share_scales).  Requires z.
+     Results are bit-for-bit those of the per-plane layout holding the same scales.       */
+  LUTGEMM_ALPHA_SHARED = 2
 };
 
 /* Buffer sizes in bytes of the packed layouts above (section 3.4 eq. 4, padded to the
@@ -105,6 +110,10 @@ enum {
 size_t lutgemm_bits_bytes(int64_t m, int64_t n, int q);
 size_t lutgemm_alpha_bytes(int64_t m, int64_t n, int q, int g);
 size_t lutgemm_z_bytes(int64_t m, int64_t n, int g);
+
+/* Bytes of the shared-scale layout: fp16 [row block][group][16 rows], index
+   ((r / 16) * NG + G) * 16 + r % 16, the layout of z.                                   */
+size_t lutgemm_alpha_shared_bytes(int64_t m, int64_t n, int g);
 
 /* Device scratch a gemv/gemm call needs: 32 KB of arrival counters, 512 KB that take
    results nobody reads, and the split-K partial sums (the per-block partial outputs that
@@ -138,6 +147,15 @@ int lutgemm_pack_planes(const int8_t* B_pm1, int64_t m, int64_t n, int q, int mu
    into the packed alpha / z layouts.                                                    */
 int lutgemm_pack_scales(const uint16_t* alpha, const uint16_t* z, int64_t m, int64_t n, int q, int g,
                         uint16_t* alpha_out, uint16_t* z_out);
+
+/* HOST.  Packed per-plane scales (as written by lutgemm_pack_bcq / lutgemm_pack_scales) ->
+   shared-scale layout, for weights whose scales satisfy alpha_i = 2^i * alpha_0 exactly in
+   every (row, group): the output of LUTGEMM_Q_UNIFORM_RTN (appendix C).  LUTGEMM_EINVAL if
+   some scale is not of that form (nothing useful is written then).  The scale bytes shrink
+   q-fold: section 3.4's footprint with one scale per group, which is what the compression
+   ratios of table 5 count.                                                              */
+int lutgemm_share_scales(const uint16_t* alpha_packed, int64_t m, int64_t n, int q, int g,
+                         uint16_t* alpha_shared_out);
 
 /* DEVICE pointers, all 16-byte aligned.  y = What * x for one activation vector
    (section 3.2: y = sum_i A_i o (B_i . x); offset term from eq. 3).
@@ -174,7 +192,8 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
    time does not grow with batch up to 16 vectors, where the lookup path's does (the
    limitation discussed in section 6), so it is the faster of the two from a batch of
    about three.  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
-   included when n % 64 == 0): LUTGEMM_EUNSUPPORTED otherwise.  Bitwise reproducible.     */
+   included when n % 64 == 0): LUTGEMM_EUNSUPPORTED otherwise, as is
+   LUTGEMM_ALPHA_SHARED.  Bitwise reproducible.                                          */
 int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
                       int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                       void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -150,15 +150,18 @@ __device__ __forceinline__ float quad_rows_reduce(const float (&acc)[4], int lan
 //   kAlphaPerSlot  one fetch per dword (slot); the two chunks of a slot share a group
 //                  (g % 16 == 0, or T == 1).
 //   kAlphaPerChunk one fetch per (dword, sub-slab): g % 16 != 0 with T == 2.
-enum { kAlphaQuad = 0, kAlphaPerSlot = 1, kAlphaPerChunk = 2 };
+// Added to any of them, kAlphaShared says that the scale buffer holds ONE value per (row,
+// group), alpha_0, and that plane i has the scale 2^i * alpha_0 (appendix C: the scales of
+// uniformly quantised weights): one fetch of four rows instead of four rows x q planes.
+enum { kAlphaQuad = 0, kAlphaPerSlot = 1, kAlphaPerChunk = 2, kAlphaShared = 4 };
 
 // What one wavefront fetches for planes I0 .. I0+QP-1 of one (K tile, row block) unit of a
 // Q-plane layer.  (Layers of up to four planes are fetched whole; more planes go in two
 // halves so that a wavefront never needs more registers than it has.)
 template <int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
 struct Unit {
-  static constexpr int NS = (AMODE == kAlphaQuad) ? 1 : 4;                 // scale sets along the dwords
-  static constexpr int NC = (AMODE == kAlphaPerChunk) ? T : 1;             // ... and along the sub-slabs
+  static constexpr int NS = ((AMODE & 3) == kAlphaQuad) ? 1 : 4;                 // scale sets along the dwords
+  static constexpr int NC = ((AMODE & 3) == kAlphaPerChunk) ? T : 1;             // ... and along the sub-slabs
   u32x4 w[QP][T];           // key words: dword s = four rows of slot 4j + (s + k) mod 4
   u32x2 al[NS][NC][QP];     // fp16 scales of the lane's four rows
   u32x2 zz[NS][NC];         // fp16 offsets of the lane's four rows (used when I0 == 0)
@@ -200,9 +203,13 @@ __device__ __forceinline__ void load_unit(Unit<Q, I0, QP, T, AMODE, HAS_Z>& u, c
 #pragma unroll
     for (int c = 0; c < U::NC; ++c) {
       const int64_t blk = (int64_t)rb * p.NG + grp[s][c];
-      const u32x2* ap = reinterpret_cast<const u32x2*>(p.alpha + ((blk * 4 + (lane & 3)) * Q) * 4);
+      if ((AMODE & kAlphaShared) != 0) {   // one scale per (row, group), laid out like the offsets
+        u.al[s][c][0] = *reinterpret_cast<const u32x2*>(p.alpha + blk * 16 + (lane & 3) * 4);
+      } else {
+        const u32x2* ap = reinterpret_cast<const u32x2*>(p.alpha + ((blk * 4 + (lane & 3)) * Q) * 4);
 #pragma unroll
-      for (int i = 0; i < QP; ++i) u.al[s][c][i] = ap[I0 + i];
+        for (int i = 0; i < QP; ++i) u.al[s][c][i] = ap[I0 + i];
+      }
       if (HAS_Z && I0 == 0) u.zz[s][c] = *reinterpret_cast<const u32x2*>(p.z + blk * 16 + (lane & 3) * 4);
     }
   // first tile of the K group: nothing to add (the value read is never used)
@@ -212,6 +219,15 @@ __device__ __forceinline__ void load_unit(Unit<Q, I0, QP, T, AMODE, HAS_Z>& u, c
 __device__ __forceinline__ float half_of(const u32x2& v, int j) {   // j-th of the 4 halves
   const uint32_t wrd = (j & 2) ? v.y : v.x;
   return (j & 1) ? half_hi(wrd) : half_lo(wrd);
+}
+
+// Scale of plane number `plane` (the i-th of the QP planes fetched together) for row rho of
+// the lane's four.  Shared layout: al[0] holds alpha_0 and the plane's scale is 2^plane times
+// it, an exact product, so the result equals that of the per-plane layout bit for bit.
+template <int AMODE, int QP>
+__device__ __forceinline__ float scale_of(const u32x2 (&al)[QP], int i, int plane, int rho) {
+  if ((AMODE & kAlphaShared) != 0) return half_of(al[0], rho) * (float)(1 << plane);
+  return half_of(al[i], rho);
 }
 
 // Lookup / accumulate / scale for the planes of u (section 3.1: partial sums are retrieved
@@ -237,11 +253,11 @@ __device__ __forceinline__ void accumulate_unit(const Unit<Q, I0, QP, T, AMODE, 
           const float v = lds_f32(__builtin_amdgcn_perm(u.w[i][t][s], lane_base[s], sel_t[t]));
           run = run_open ? run + v : v;
           run_open = true;
-          const bool close = (AMODE == kAlphaPerChunk) || (AMODE == kAlphaPerSlot && t == T - 1) ||
+          const bool close = ((AMODE & 3) == kAlphaPerChunk) || ((AMODE & 3) == kAlphaPerSlot && t == T - 1) ||
                              (s == 3 && t == T - 1);
           if (close) {
-            const int ss = (AMODE == kAlphaQuad) ? 0 : s, cc = (AMODE == kAlphaPerChunk) ? t : 0;
-            acc[rho] = fmaf(half_of(u.al[ss][cc][i], rho), run, acc[rho]);
+            const int ss = ((AMODE & 3) == kAlphaQuad) ? 0 : s, cc = ((AMODE & 3) == kAlphaPerChunk) ? t : 0;
+            acc[rho] = fmaf(scale_of<AMODE>(u.al[ss][cc], i, I0 + i, rho), run, acc[rho]);
             run_open = false;
           }
         }
@@ -254,13 +270,13 @@ __device__ __forceinline__ void accumulate_unit(const Unit<Q, I0, QP, T, AMODE, 
 #pragma unroll
       for (int c = 0; c < U::NC; ++c) {
         float sx;
-        if (AMODE == kAlphaQuad) {
+        if ((AMODE & 3) == kAlphaQuad) {
           sx = 0.0f;
 #pragma unroll
           for (int s2 = 0; s2 < 4; ++s2)
 #pragma unroll
             for (int t = 0; t < T; ++t) sx += sum_x[s2][t];
-        } else if (AMODE == kAlphaPerSlot) {
+        } else if ((AMODE & 3) == kAlphaPerSlot) {
           sx = (T == 2) ? sum_x[s][0] + sum_x[s][T - 1] : sum_x[s][0];
         } else {
           sx = sum_x[s][c];
@@ -391,7 +407,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   // Planes fetched together: all of them for up to four planes, about half for more; one
   // at a time when every (dword, sub-slab) has a scale set of its own.  Keeps a wavefront
   // within its registers in every variant.
-  constexpr int PP = (AMODE == kAlphaPerChunk) ? 1 : (Q > 4 ? (Q + 1) / 2 : Q);
+  constexpr int PP = ((AMODE & 3) == kAlphaPerChunk) ? 1 : (Q > 4 ? (Q + 1) / 2 : Q);
   if constexpr (PP < Q) {
     // ---- several fetches per unit, no fetch-ahead ----
     u32x4 xraw[kBuildPasses];
@@ -536,7 +552,7 @@ constexpr int prefetch_depth(int q, int amode) {
   return LUT_DEPTH;
 #else
   if (kWaves > 8) return 0;
-  return (amode == kAlphaQuad && q <= 4) || (amode == kAlphaPerSlot && q <= 3) ? 1 : 0;   // q > 4: unused
+  return ((amode & 3) == kAlphaQuad && q <= 4) || ((amode & 3) == kAlphaPerSlot && q <= 3) ? 1 : 0;   // q > 4: unused
 #endif
 }
 
@@ -628,11 +644,11 @@ __device__ __forceinline__ void accumulate_pair(const Unit<Q, I0, QP, 1, AMODE, 
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         const f32x2 e = lds_f32x2(__builtin_amdgcn_perm(u.w[i][0][s], lane_base[s], sel));
-        const bool first = (AMODE == kAlphaQuad) ? (s == 0) : true;
+        const bool first = ((AMODE & 3) == kAlphaQuad) ? (s == 0) : true;
         run0 = first ? e.x : run0 + e.x;
         run1 = first ? e.y : run1 + e.y;
-        if (AMODE != kAlphaQuad || s == 3) {   // section 3.2 rule 2: one scale per run of lookups
-          const float a = half_of(u.al[(AMODE == kAlphaQuad) ? 0 : s][0][i], rho);
+        if ((AMODE & 3) != kAlphaQuad || s == 3) {   // section 3.2 rule 2: one scale per run of lookups
+          const float a = scale_of<AMODE>(u.al[((AMODE & 3) == kAlphaQuad) ? 0 : s][0], i, I0 + i, rho);
           acc[0][rho] = fmaf(a, run0, acc[0][rho]);
           acc[1][rho] = fmaf(a, run1, acc[1][rho]);
         }
@@ -643,7 +659,7 @@ __device__ __forceinline__ void accumulate_pair(const Unit<Q, I0, QP, 1, AMODE, 
 #pragma unroll
     for (int s = 0; s < U::NS; ++s) {
       f32x2 sx = sum_x[s];
-      if (AMODE == kAlphaQuad) sx = (sum_x[0] + sum_x[1]) + (sum_x[2] + sum_x[3]);
+      if ((AMODE & 3) == kAlphaQuad) sx = (sum_x[0] + sum_x[1]) + (sum_x[2] + sum_x[3]);
 #pragma unroll
       for (int rho = 0; rho < 4; ++rho) {
         const float zf = half_of(u.zz[s][0], rho);
@@ -698,7 +714,8 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
   // unit is the key words plus a scale set (and offsets) per dword when the scales are not
   // shared by the quad.  A unit is only 1 KB per plane, so it takes two of them in flight
   // per wavefront to cover the memory latency at full bandwidth.
-  constexpr int kUnitRegs = 4 * Q + (AMODE == kAlphaQuad ? 2 * Q : 8 * Q + (HAS_Z ? 8 : 0));
+  constexpr int kScaleRegs = (AMODE & kAlphaShared) ? 2 : 2 * Q;   // per scale set
+  constexpr int kUnitRegs = 4 * Q + ((AMODE & 3) == kAlphaQuad ? kScaleRegs : 4 * kScaleRegs + (HAS_Z ? 8 : 0));
   constexpr int kFit = (PP < Q || kUnitRegs > 36) ? 0 : (kUnitRegs > 24 ? 1 : 2);
   constexpr int D = kFit < kDepth ? kFit : kDepth;
   const int n_units = rb1 - rb0;
@@ -893,16 +910,18 @@ GemvKernel pick_q(int q) {
 #endif
 }
 
-template <bool HAS_Z>
+template <bool HAS_Z, int SH>
 GemvKernel pick_mode(int q, int64_t g) {
-  if (g % 64 == 0) return pick_q<HAS_Z, kAlphaQuad, kAlphaQuad>(q);
-  if (g % 32 == 0) return pick_q<HAS_Z, kAlphaPerSlot, kAlphaQuad>(q);
-  if (g % 16 == 0) return pick_q<HAS_Z, kAlphaPerSlot, kAlphaPerSlot>(q);
-  return pick_q<HAS_Z, kAlphaPerChunk, kAlphaPerSlot>(q);
+  if (g % 64 == 0) return pick_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
+  if (g % 32 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
+  if (g % 16 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
+  return pick_q<HAS_Z, kAlphaPerChunk | SH, kAlphaPerSlot | SH>(q);
 }
 
-GemvKernel pick_kernel(int q, bool has_z, int64_t g) {
-  return has_z ? pick_mode<true>(q, g) : pick_mode<false>(q, g);
+// shared: the scale buffer is in the shared-scale layout (offsets are then always present)
+GemvKernel pick_kernel(int q, bool has_z, bool shared, int64_t g) {
+  if (shared) return pick_mode<true, kAlphaShared>(q, g);
+  return has_z ? pick_mode<true, 0>(q, g) : pick_mode<false, 0>(q, g);
 }
 
 // Pair kernel: a lane's dword is one chunk, so the per-chunk scale mode does not occur.
@@ -925,17 +944,18 @@ GemvKernel pick_pair_q(int q) {
 #endif
 }
 
-template <bool HAS_Z>
+template <bool HAS_Z, int SH>
 GemvKernel pick_pair_mode(int q, int64_t g) {
   // quad mode needs the quad's four chunks of one sub-slab in one group: they span 56 columns
   // of an aligned 64 in a two-sub-slab tile, 32 columns in a one-sub-slab tile
-  if (g % 64 == 0) return pick_pair_q<HAS_Z, kAlphaQuad, kAlphaQuad>(q);
-  if (g % 32 == 0) return pick_pair_q<HAS_Z, kAlphaPerSlot, kAlphaQuad>(q);
-  return pick_pair_q<HAS_Z, kAlphaPerSlot, kAlphaPerSlot>(q);
+  if (g % 64 == 0) return pick_pair_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
+  if (g % 32 == 0) return pick_pair_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
+  return pick_pair_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
 }
 
-GemvKernel pick_pair_kernel(int q, bool has_z, int64_t g) {
-  return has_z ? pick_pair_mode<true>(q, g) : pick_pair_mode<false>(q, g);
+GemvKernel pick_pair_kernel(int q, bool has_z, bool shared, int64_t g) {
+  if (shared) return pick_pair_mode<true, kAlphaShared>(q, g);
+  return has_z ? pick_pair_mode<true, 0>(q, g) : pick_pair_mode<false, 0>(q, g);
 }
 
 int compute_units() {
@@ -1105,8 +1125,10 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   if (gg % 8 != 0 || n % gg != 0) return LUTGEMM_EINVAL;
   if (!aligned16(x) || !aligned16(bits) || !aligned16(alpha) || !aligned16(z) || !aligned16(y) || !aligned16(workspace))
     return LUTGEMM_EINVAL;
-  if (mu != 8 || batch > 32 || (flags & ~1u) != 0) return LUTGEMM_EUNSUPPORTED;
+  if (mu != 8 || batch > 32 || (flags & ~3u) != 0) return LUTGEMM_EUNSUPPORTED;
   if (m > (int64_t)1 << 30 || n > (int64_t)1 << 30) return LUTGEMM_EUNSUPPORTED;
+  const bool shared = (flags & LUTGEMM_ALPHA_SHARED) != 0;
+  if (shared && !z) return LUTGEMM_EINVAL;   // the shared-scale form always comes with offsets
   const size_t need = lutgemm_workspace_bytes(m, n, q, g, mu, batch);
   if (need == 0) return LUTGEMM_EINVAL;
   if (workspace_bytes < need) return LUTGEMM_EWORKSPACE;
@@ -1130,7 +1152,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   const int64_t m_pad = (int64_t)p.RB * 16;
   p.kg_stride = m_pad * batch;
 
-  GemvKernel kern = pick_kernel(q, z != nullptr, gg);
+  GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
 
   uint32_t* counters = static_cast<uint32_t*>(workspace);
@@ -1147,7 +1169,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     const int last_chunks = p.nchunks - 128 * (p.NT - 1);
     pp.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);
     plan_grid(cus, true, "LUTGEMM_PAIR_TPG", "LUTGEMM_PAIR_RS", &pp);
-    pair_kern = pick_pair_kernel(q, z != nullptr, gg);
+    pair_kern = pick_pair_kernel(q, z != nullptr, shared, gg);
     if (!pair_kern) return LUTGEMM_EUNSUPPORTED;
   }
   for (int b = 0; b < batch;) {

@@ -171,6 +171,24 @@ size_t lutgemm_z_bytes(int64_t m, int64_t n, int g) {
   return (size_t)s.RB * s.NG * kRowsPerBlock * 2;
 }
 
+size_t lutgemm_alpha_shared_bytes(int64_t m, int64_t n, int g) { return lutgemm_z_bytes(m, n, g); }
+
+int lutgemm_share_scales(const uint16_t* alpha_packed, int64_t m, int64_t n, int q, int g,
+                         uint16_t* alpha_shared_out) {
+  Shape s;
+  if (!alpha_packed || !alpha_shared_out || !make_shape(m, n, q, g, &s)) return LUTGEMM_EINVAL;
+  for (int64_t rb = 0; rb < s.RB; ++rb)
+    for (int64_t gi = 0; gi < s.NG; ++gi)
+      for (int64_t rho = 0; rho < kRowsPerBlock; ++rho) {
+        const uint16_t* a = alpha_packed + (((rb * s.NG + gi) * 4 + rho / 4) * q) * 4 + rho % 4;   // plane i at a[4 * i]
+        const float a0 = half_to_float(a[0]);
+        for (int i = 1; i < q; ++i)
+          if (half_to_float(a[4 * i]) != std::ldexp(a0, i)) return LUTGEMM_EINVAL;
+        alpha_shared_out[(rb * s.NG + gi) * kRowsPerBlock + rho] = a[0];
+      }
+  return LUTGEMM_OK;
+}
+
 size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch) {
   Shape s;
   if (mu != 8 || batch < 1 || batch > 32 || !make_shape(m, n, q, g, &s)) return 0;

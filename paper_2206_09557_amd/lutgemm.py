@@ -14,13 +14,15 @@ LIB_PATH = os.path.join(_PKG, "liblutgemm.so")
 
 LUTGEMM_OK, LUTGEMM_EINVAL, LUTGEMM_EUNSUPPORTED, LUTGEMM_EWORKSPACE, LUTGEMM_EHIP = 0, -1, -2, -3, -4
 LUTGEMM_Q_GREEDY, LUTGEMM_Q_GREEDY_MEAN_OFFSET, LUTGEMM_Q_UNIFORM_RTN = 0, 1, 2
-LUTGEMM_Y_F16, LUTGEMM_Y_F32 = 0, 1
+LUTGEMM_Y_F16, LUTGEMM_Y_F32, LUTGEMM_ALPHA_SHARED = 0, 1, 2
 
 _c = ctypes
 _SIGNATURES = {
     "lutgemm_bits_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64, _c.c_int]),
     "lutgemm_alpha_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64, _c.c_int, _c.c_int]),
     "lutgemm_z_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64, _c.c_int]),
+    "lutgemm_alpha_shared_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64, _c.c_int]),
+    "lutgemm_share_scales": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int, _c.c_int, _c.c_void_p]),
     "lutgemm_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64, _c.c_int, _c.c_int, _c.c_int, _c.c_int]),
     "lutgemm_pack_bcq": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                     _c.c_void_p, _c.c_void_p, _c.c_void_p]),
@@ -102,6 +104,10 @@ def lutgemm_z_bytes(m, n, g):
     return lib().lutgemm_z_bytes(m, n, g)
 
 
+def lutgemm_alpha_shared_bytes(m, n, g):
+    return lib().lutgemm_alpha_shared_bytes(m, n, g)
+
+
 def lutgemm_workspace_bytes(m, n, q, g, mu=8, batch=1):
     return lib().lutgemm_workspace_bytes(m, n, q, g, mu, batch)
 
@@ -159,6 +165,17 @@ def lutgemm_pack_scales(alpha, z, n, g):
     _check(lib().lutgemm_pack_scales(alpha.ctypes.data, _addr(z), m, n, q, g, ap.ctypes.data, _addr(zp)),
            "lutgemm_pack_scales")
     return ap, zp
+
+
+def lutgemm_share_scales(alpha_packed, m, n, q, g):
+    """Packed per-plane scales (numpy fp16) -> shared-scale layout (numpy fp16)."""
+    alpha_packed = np.ascontiguousarray(alpha_packed, dtype=np.float16)
+    ns = lutgemm_alpha_shared_bytes(m, n, g)
+    if ns == 0 or alpha_packed.nbytes != lutgemm_alpha_bytes(m, n, q, g):
+        raise LutGemmError(LUTGEMM_EINVAL, "lutgemm_share_scales")
+    out = np.empty(ns // 2, dtype=np.float16)
+    _check(lib().lutgemm_share_scales(alpha_packed.ctypes.data, m, n, q, g, out.ctypes.data), "lutgemm_share_scales")
+    return out
 
 
 # ---- device --------------------------------------------------------------------------

@@ -21,6 +21,9 @@ def main(argv=None):
     ap.add_argument("--iters", type=int, default=50)
     ap.add_argument("--q", type=str, default="1,2,3,4,5,6,7,8")
     ap.add_argument("--g", type=str, default="32,64,128,256,0")
+    ap.add_argument("--layout", choices=["planes", "planes_z", "shared"], default="planes",
+                    help="planes: q scales per group (eq. 4); planes_z: plus one offset per group; "
+                         "shared: one scale and one offset per group (uniformly quantised weights, appendix C)")
     args = ap.parse_args(argv)
 
     import torch
@@ -39,16 +42,21 @@ def main(argv=None):
     rows = []
     for q in [int(v) for v in args.q.split(",")]:
         for g in [int(v) for v in args.g.split(",")]:
-            nb, na = L.lutgemm_bits_bytes(m, n, q), L.lutgemm_alpha_bytes(m, n, q, g)
-            copies = max(2, min(8, int(1.2e9 // (nb + na)) or 2))
+            nb = L.lutgemm_bits_bytes(m, n, q)
+            na = L.lutgemm_alpha_shared_bytes(m, n, g) if args.layout == "shared" else L.lutgemm_alpha_bytes(m, n, q, g)
+            nz = 0 if args.layout == "planes" else L.lutgemm_z_bytes(m, n, g)
+            copies = max(2, min(8, int(1.2e9 // (nb + na + nz)) or 2))
             bits = [torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=gen) for _ in range(copies)]
             alpha = [(torch.rand(na // 2, device="cuda", generator=gen) * 0.05 + 0.001).half() for _ in range(copies)]
+            zs = [None] * copies if nz == 0 else [(torch.rand(nz // 2, device="cuda", generator=gen) * 0.02 - 0.01).half()
+                                                  for _ in range(copies)]
+            flags = L.LUTGEMM_Y_F16 | (L.LUTGEMM_ALPHA_SHARED if args.layout == "shared" else 0)
             wsb = L.lutgemm_workspace_bytes(m, n, q, g)
             ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
             L.lutgemm_workspace_init(ws, wsb, stream)
 
             def go(i):
-                L.lutgemm_gemv(x, bits[i % copies], alpha[i % copies], None, y, q, g, 8, m, n, L.LUTGEMM_Y_F16, ws, wsb,
+                L.lutgemm_gemv(x, bits[i % copies], alpha[i % copies], zs[i % copies], y, q, g, 8, m, n, flags, ws, wsb,
                                stream)
 
             for i in range(5):
@@ -61,11 +69,13 @@ def main(argv=None):
             torch.cuda.synchronize()
             us = a.elapsed_time(b) * 1e3 / args.iters
             gg = n if g == 0 else g
-            footprint = m * n * q // 8 + 2 * m * (n // gg) * q      # eq. 4 in bytes
+            footprint = m * n * q // 8 + na + nz                    # bits + scales (+ offsets), bytes
             rows.append((q, g, footprint, us))
-            del bits, alpha, ws
+            del bits, alpha, zs, ws
             print(f"[sweep] q={q} g={g or 'row'}: {us:.2f} us", file=sys.stderr, flush=True)
-    print(f"| q | g | footprint MB (eq. 4) | us / GEMV | GB/s | us per MB |")
+    print(f"layout: {args.layout}, m = {m}, n = {n}")
+    print()
+    print(f"| q | g | footprint MB | us / GEMV | GB/s | us per MB |")
     print("|---|---|---|---|---|---|")
     for q, g, fp, us in rows:
         print(f"| {q} | {g or 'row'} | {fp / 1e6:.2f} | {us:.2f} | {fp / us / 1e3:.0f} | {us / (fp / 1e6):.3f} |")

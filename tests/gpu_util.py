@@ -22,6 +22,13 @@ class Packed:
         self.d_alpha = torch.from_numpy(alpha.view(np.int16)).cuda()
         self.d_z = None if z is None else torch.from_numpy(z.view(np.int16)).cuda()
 
+    def share(self):
+        """Also hold the scales in the shared-scale layout (uniformly quantised layers)."""
+        torch = torch_cuda()
+        self.alpha_shared = L.lutgemm_share_scales(self.alpha, self.m, self.n, self.q, self.g)
+        self.d_alpha_shared = torch.from_numpy(self.alpha_shared.view(np.int16)).cuda()
+        return self
+
     @classmethod
     def from_weights(cls, W, q, g, mode=L.LUTGEMM_Q_GREEDY):
         bits, alpha, z = L.lutgemm_pack_bcq(W, q, g, mode=mode)
@@ -41,7 +48,7 @@ def make_workspace(nbytes, stream=None):
     return d_ws
 
 
-def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False):
+def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, shared=False):
     """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x; lutgemm_gemm_mfma if mfma) for the packed layer.
     y is pre-filled with NaN: it must be fully overwritten, never read."""
     torch = torch_cuda()
@@ -56,15 +63,19 @@ def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False):
     assert d_ws.numel() >= wsb
     s = torch.cuda.current_stream() if stream is None else stream
     flags = L.LUTGEMM_Y_F32 if f32_out else L.LUTGEMM_Y_F16
+    d_alpha = p.d_alpha
+    if shared:   # scales in the shared-scale layout
+        flags |= L.LUTGEMM_ALPHA_SHARED
+        d_alpha = p.d_alpha_shared
     torch.cuda.synchronize()
     if mfma:
-        L.lutgemm_gemm_mfma(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
+        L.lutgemm_gemm_mfma(d_x, p.d_bits, d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
                             d_ws.numel(), s.cuda_stream)
     elif x16.ndim == 1:
-        L.lutgemm_gemv(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, flags, d_ws, d_ws.numel(),
+        L.lutgemm_gemv(d_x, p.d_bits, d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, flags, d_ws, d_ws.numel(),
                        s.cuda_stream)
     else:
-        L.lutgemm_gemm(d_x, p.d_bits, p.d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
+        L.lutgemm_gemm(d_x, p.d_bits, d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
                        d_ws.numel(), s.cuda_stream)
     s.synchronize()
     y = d_y.cpu().numpy()

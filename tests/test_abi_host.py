@@ -131,7 +131,8 @@ def test_argument_validation_returns_codes_without_gpu():
     assert gemv(g=12, n=96) == L.LUTGEMM_EINVAL              # g % 8
     assert gemv(q=0) == L.LUTGEMM_EINVAL and gemv(q=9) == L.LUTGEMM_EINVAL
     assert gemv(mu=4) == L.LUTGEMM_EUNSUPPORTED
-    assert gemv(flags=2) == L.LUTGEMM_EUNSUPPORTED
+    assert gemv(flags=4) == L.LUTGEMM_EUNSUPPORTED           # unknown flag
+    assert gemv(flags=2) == L.LUTGEMM_EINVAL                 # shared-scale layout without offsets
     assert gemv(wsb=16) == L.LUTGEMM_EWORKSPACE
     assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 33, 0, p16, 1 << 20, None) == L.LUTGEMM_EUNSUPPORTED
     assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 0, 0, p16, 1 << 20, None) == L.LUTGEMM_EINVAL
@@ -142,3 +143,20 @@ def test_argument_validation_returns_codes_without_gpu():
     assert lib.lutgemm_workspace_init(None, 1 << 20, None) == L.LUTGEMM_EINVAL
     assert lib.lutgemm_workspace_init(p16, 1024, None) == L.LUTGEMM_EWORKSPACE
     assert lib.lutgemm_strerror(L.LUTGEMM_EWORKSPACE) == b"workspace too small"
+
+
+def test_share_scales_is_bit_exact_against_oracle_and_rejects_other_scales():
+    # appendix C: the scales of a uniformly quantised group are alpha_i = 2^i * alpha_0
+    m, n, q, g = 37, 1536, 4, 64
+    W = synth.weights_fp16(m, n, seed=77)
+    bits, alpha_p, z_p = L.lutgemm_pack_bcq(W, q, g, mode=L.LUTGEMM_Q_UNIFORM_RTN)
+    shared = L.lutgemm_share_scales(alpha_p, m, n, q, g)
+    assert shared.nbytes == L.lutgemm_alpha_shared_bytes(m, n, g) == L.lutgemm_z_bytes(m, n, g)
+    alpha = O.decode_alpha(alpha_p, m, n // g, q)
+    want = O.encode_alpha_shared(O.share_scales(alpha))
+    np.testing.assert_array_equal(shared.view(np.uint16), want.view(np.uint16))
+    # greedy scales are not powers of two apart
+    _, alpha_g, _ = L.lutgemm_pack_bcq(W, 3, g)
+    with pytest.raises(L.LutGemmError) as e:
+        L.lutgemm_share_scales(alpha_g, m, n, 3, g)
+    assert e.value.code == L.LUTGEMM_EINVAL

@@ -189,3 +189,46 @@ def test_mfma_path_rejects_groups_not_multiple_of_64():
     with pytest.raises(L.LutGemmError) as e:
         run(p, X, mfma=True)
     assert e.value.code == L.LUTGEMM_EUNSUPPORTED
+
+
+# ---- shared-scale layout (one scale per group, appendix C) ----
+
+SHARED_CASES = [
+    (300, 2048, 3, 32, None),     # small groups: the scale bytes matter most here
+    (300, 2048, 2, 64, None),
+    (1000, 1536, 4, 128, None),   # last tile with one sub-slab
+    (96, 1048, 3, 8, None),       # per-chunk scale fetches, ragged tile
+    (130, 1032, 5, 24, None),     # more than four planes (fetched in two halves)
+    (77, 520, 8, 0, None),        # row-wise, eight planes
+    (4100, 3072, 3, 128, 5),      # batch: pairs and an odd last vector
+    (333, 2048, 4, 32, 2),
+]
+
+
+@pytest.mark.parametrize("m,n,q,g,batch", SHARED_CASES)
+def test_shared_scales_equal_per_plane_scales_bitwise(m, n, q, g, batch):
+    print(f"case shared m={m} n={n} q={q} g={g} batch={batch}", flush=True)
+    W = synth.weights_fp16(m, n, seed=7000 + m + 7 * n + q)
+    x = synth.activations_fp16(n, seed=7500 + m + n, batch=batch)
+    p = Packed.from_weights(W, q, g, L.LUTGEMM_Q_UNIFORM_RTN).share()
+    y_planes = run(p, x, f32_out=True)
+    y_shared = run(p, x, f32_out=True, shared=True)
+    np.testing.assert_array_equal(y_shared, y_planes)
+    np.testing.assert_array_equal(run(p, x, shared=True), run(p, x))
+    # and against the oracle reading the shared layout itself
+    bound = _bound(p)
+    xs = x if batch else x[None, :]
+    ys = y_shared if batch else y_shared[None, :]
+    for b in range(xs.shape[0]):
+        y_ref = O.gemv_packed(p.bits, p.alpha_shared, p.z, xs[b], m, n, q, g, alpha_shared=True)
+        check_parity(ys[b], y_ref, xs[b], bound, f32_out=True)
+
+
+def test_shared_scales_need_offsets():
+    m, n, q, g = 64, 1024, 2, 64
+    W = synth.weights_fp16(m, n, seed=7900)
+    p = Packed.from_weights(W, q, g, L.LUTGEMM_Q_UNIFORM_RTN).share()
+    p.d_z = None
+    with pytest.raises(L.LutGemmError) as e:
+        run(p, synth.activations_fp16(n, seed=7901), shared=True)
+    assert e.value.code == L.LUTGEMM_EINVAL
