@@ -232,3 +232,50 @@ def test_shared_scales_need_offsets():
     with pytest.raises(L.LutGemmError) as e:
         run(p, synth.activations_fp16(n, seed=7901), shared=True)
     assert e.value.code == L.LUTGEMM_EINVAL
+
+
+# ---- seeded sweep over random small shapes: every path against the oracle ----
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        q = int(rng.integers(1, 9))
+        g_units = int(rng.choice([1, 2, 3, 4, 8, 16, 24]))          # group size in chunks of 8 columns
+        groups = int(rng.integers(1, 40))
+        n = 8 * g_units * groups
+        if n > 4096:
+            continue
+        g = 0 if rng.random() < 0.15 else 8 * g_units
+        m = int(rng.integers(1, 400))
+        mode = ["greedy", "greedy_z", "rtn"][int(rng.integers(0, 3))]
+        batch = [None, None, 2, 3, 7, 18][int(rng.integers(0, 6))]
+        cases.append((m, n, q, g, mode, batch))
+    return cases
+
+
+@pytest.mark.parametrize("m,n,q,g,mode,batch", _random_cases(36, 20240607))
+def test_random_shapes_all_paths(m, n, q, g, mode, batch):
+    print(f"case random m={m} n={n} q={q} g={g} mode={mode} batch={batch}", flush=True)
+    W = synth.weights_fp16(m, n, seed=8000 + m + 3 * n + q)
+    x = synth.activations_fp16(n, seed=8500 + m + n, batch=batch)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    bound = _bound(p)
+    xs = x if batch else x[None, :]
+    refs = [_oracle_full(p, xs[b]) for b in range(xs.shape[0])]
+
+    def check(y):
+        ys = y if batch else y[None, :]
+        for b in range(xs.shape[0]):
+            check_parity(ys[b], refs[b], xs[b], bound, f32_out=True)
+
+    y = run(p, x, f32_out=True)
+    check(y)
+    gg = n if g == 0 else g
+    if gg % 64 == 0:                       # the matrix-core path takes these group sizes only
+        ym = run(p, xs, f32_out=True, mfma=True)
+        for b in range(xs.shape[0]):
+            check_parity(ym[b], refs[b], xs[b], bound, f32_out=True)
+    if mode == "rtn":                      # shared-scale layout: bitwise the same as per-plane scales
+        p.share()
+        np.testing.assert_array_equal(run(p, x, f32_out=True, shared=True), y)
