@@ -163,6 +163,122 @@ def quantize_greedy(W16, q, g, mean_offset=False):
     return B, alpha, z
 
 
+def _solve_in_order(G, c):
+    """Solve G a = c (q x q, fp64) by Gaussian elimination with partial pivoting, every
+    operation in a fixed order (the packer does the same arithmetic).  None if singular."""
+    q = len(c)
+    A = [[float(G[i][j]) for j in range(q)] + [float(c[i])] for i in range(q)]
+    for col in range(q):
+        piv = col
+        for r in range(col + 1, q):
+            if abs(A[r][col]) > abs(A[piv][col]):
+                piv = r
+        if abs(A[piv][col]) < 1e-9:
+            return None
+        A[col], A[piv] = A[piv], A[col]
+        for r in range(col + 1, q):
+            f = A[r][col] / A[col][col]
+            for j in range(col, q + 1):
+                A[r][j] = A[r][j] - f * A[col][j]
+    a = [0.0] * q
+    for i in range(q - 1, -1, -1):
+        acc = A[i][q]
+        for j in range(i + 1, q):
+            acc = acc - A[i][j] * a[j]
+        a[i] = acc / A[i][i]
+    return a
+
+
+def _assign_codes(w, a):
+    """For every weight the sign pattern (code: bit i = plane i is +1) whose level
+    sum_i +-a_i is nearest; ties go to the smallest code.  Levels are summed in plane order."""
+    q = len(a)
+    levels = []
+    for code in range(1 << q):
+        v = 0.0
+        for i in range(q):
+            v = v + (a[i] if (code >> i) & 1 else -a[i])
+        levels.append(v)
+    codes = np.zeros(len(w), dtype=np.int64)
+    for k, wk in enumerate(w):
+        best, best_d = 0, abs(wk - levels[0])
+        for code in range(1, 1 << q):
+            d = abs(wk - levels[code])
+            if d < best_d:
+                best, best_d = code, d
+        codes[k] = best
+    return codes
+
+
+def quantize_alternating_group(w16, q, iters=15):
+    """Alternating BCQ of one group (the iterative solver the paper's appendix on compression
+    ratios cites for obtaining BCQ weights): start from the greedy solution in fp64; then
+    repeat { scales = least-squares fit for the current signs; planes with a negative scale
+    are negated; every weight takes the nearest of the 2^q levels } until the signs stop
+    changing or `iters` rounds have run; finally round the scales to fp16 and assign the
+    signs once more for the stored scales.  Returns (b int8 [q][g], alpha fp16 [q])."""
+    w = [float(v) for v in np.asarray(w16, dtype=np.float16).astype(np.float64)]
+    g = len(w)
+    r = list(w)
+    b = [[0] * g for _ in range(q)]
+    a = [0.0] * q
+    for i in range(q):                                   # greedy start, fp64, sums in index order
+        s = 0.0
+        for k in range(g):
+            b[i][k] = 1 if r[k] >= 0 else -1
+            s = s + abs(r[k])
+        a[i] = s / g
+        for k in range(g):
+            r[k] = r[k] - a[i] * b[i][k]
+    for _ in range(iters):
+        G = [[0.0] * q for _ in range(q)]
+        c = [0.0] * q
+        for i in range(q):
+            for j in range(q):
+                t = 0
+                for k in range(g):
+                    t += b[i][k] * b[j][k]
+                G[i][j] = float(t)
+            t = 0.0
+            for k in range(g):
+                t = t + b[i][k] * w[k]
+            c[i] = t
+        sol = _solve_in_order(G, c)
+        if sol is None:                                  # two planes coincide: keep what we have
+            break
+        a = sol
+        for i in range(q):
+            if a[i] < 0:
+                a[i] = -a[i]
+                b[i] = [-v for v in b[i]]
+        codes = _assign_codes(w, a)
+        nb = [[1 if (int(codes[k]) >> i) & 1 else -1 for k in range(g)] for i in range(q)]
+        if nb == b:
+            break
+        b = nb
+    a16 = np.array(a, dtype=np.float64).astype(np.float16)
+    codes = _assign_codes(w, [float(v) for v in a16.astype(np.float64)])
+    B = np.array([[1 if (int(codes[k]) >> i) & 1 else -1 for k in range(g)] for i in range(q)], dtype=np.int8)
+    return B, a16
+
+
+def quantize_alternating(W16, q, g, iters=15):
+    """Alternating BCQ of an fp16 matrix, group by group.  Returns (B int8 [q][m][n],
+    alpha fp16 [q][m][NG], None)."""
+    W16 = np.asarray(W16, dtype=np.float16)
+    m, n = W16.shape
+    g = n if g == 0 else g
+    NG = n // g
+    B = np.empty((q, m, n), dtype=np.int8)
+    alpha = np.empty((q, m, NG), dtype=np.float16)
+    for r in range(m):
+        for G in range(NG):
+            b, a = quantize_alternating_group(W16[r, G * g:(G + 1) * g], q, iters)
+            B[:, r, G * g:(G + 1) * g] = b
+            alpha[:, r, G] = a
+    return B, alpha, None
+
+
 def quantize_uniform_rtn(W16, q, g):
     """Asymmetric min/max round-to-nearest, converted to BCQ as appendix C states."""
     W16 = np.asarray(W16, dtype=np.float16)
