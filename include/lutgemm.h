@@ -91,7 +91,18 @@ enum {
      rounding), u = clamp(rint((w - zhat) / s), 0, 2^q - 1) in fp32, plane i = bit i of u,
      alpha_i = fp16(2^(i-1) * s), z = fp16(zhat + sum_i alpha_i) (fp32 sum over the stored
      alpha_i, i ascending, then + zhat).  If s == 0 every bit is 1, alpha_i = 0, z = zhat. */
-  LUTGEMM_Q_UNIFORM_RTN = 2
+  LUTGEMM_Q_UNIFORM_RTN = 2,
+  /* Alternating BCQ, no offset: the iterative solver the paper's appendix on compression
+     ratios cites for obtaining BCQ weights.  Per (row, group), all in fp64 with every sum in
+     index order: start from the greedy solution (unrounded scales); then up to 15 rounds of
+     { scales = least-squares fit for the current signs (normal equations, Gaussian
+     elimination with partial pivoting; stop if singular); a plane whose scale comes out
+     negative is negated; every weight takes the nearest of the 2^q levels sum_i +-alpha_i
+     (levels summed in plane order, ties to the smallest code, bit i of the code = plane i
+     is +1) }, stopping early when no sign changes; finally the scales are rounded to fp16
+     and the signs assigned once more for the stored scales.  Never worse than the greedy
+     start before the rounding; cost grows with 2^q per weight and round.                 */
+  LUTGEMM_Q_ALTERNATING = 3
 };
 
 /* `flags` of lutgemm_gemv / lutgemm_gemm. */

@@ -149,6 +149,110 @@ inline double seq_sum(const float* r, int64_t g) {
   return s;
 }
 
+// ---- alternating BCQ (mode LUTGEMM_Q_ALTERNATING): fp64 throughout, every sum in index order ----
+
+// G a = c by Gaussian elimination with partial pivoting; false if singular.
+inline bool solve_in_order(int q, double (&A)[8][9], double (&a)[8]) {
+  for (int col = 0; col < q; ++col) {
+    int piv = col;
+    for (int r = col + 1; r < q; ++r)
+      if (std::fabs(A[r][col]) > std::fabs(A[piv][col])) piv = r;
+    if (std::fabs(A[piv][col]) < 1e-9) return false;
+    if (piv != col)
+      for (int j = 0; j <= q; ++j) std::swap(A[col][j], A[piv][j]);
+    for (int r = col + 1; r < q; ++r) {
+      const double f = A[r][col] / A[col][col];
+      for (int j = col; j <= q; ++j) A[r][j] = A[r][j] - f * A[col][j];
+    }
+  }
+  for (int i = q - 1; i >= 0; --i) {
+    double acc = A[i][q];
+    for (int j = i + 1; j < q; ++j) acc = acc - A[i][j] * a[j];
+    a[i] = acc / A[i][i];
+  }
+  return true;
+}
+
+// Nearest of the 2^q levels sum_i +-a_i for every weight; ties to the smallest code.
+inline void assign_codes(const double* w, int64_t g, int q, const double (&a)[8], int* code) {
+  double levels[256];
+  for (int c = 0; c < (1 << q); ++c) {
+    double v = 0.0;
+    for (int i = 0; i < q; ++i) v = v + (((c >> i) & 1) ? a[i] : -a[i]);
+    levels[c] = v;
+  }
+  for (int64_t k = 0; k < g; ++k) {
+    int best = 0;
+    double best_d = std::fabs(w[k] - levels[0]);
+    for (int c = 1; c < (1 << q); ++c) {
+      const double d = std::fabs(w[k] - levels[c]);
+      if (d < best_d) {
+        best = c;
+        best_d = d;
+      }
+    }
+    code[k] = best;
+  }
+}
+
+// One group: greedy start, then { least-squares scales for the signs; planes with a negative
+// scale negated; nearest level per weight } until the signs stop changing or kAltIters rounds;
+// scales rounded to fp16, signs assigned once more for the stored scales.
+constexpr int kAltIters = 15;
+inline void alternating_group(const double* w, int64_t g, int q, std::vector<int>& code, std::vector<int>& code_new,
+                              std::vector<double>& r, uint16_t (&a16)[8]) {
+  double a[8];
+  for (int64_t k = 0; k < g; ++k) {
+    r[k] = w[k];
+    code[k] = 0;
+  }
+  for (int i = 0; i < q; ++i) {
+    double sum = 0.0;
+    for (int64_t k = 0; k < g; ++k) {
+      if (r[k] >= 0.0) code[k] |= 1 << i;
+      sum = sum + std::fabs(r[k]);
+    }
+    a[i] = sum / (double)g;
+    for (int64_t k = 0; k < g; ++k) r[k] = r[k] - a[i] * (((code[k] >> i) & 1) ? 1.0 : -1.0);
+  }
+  for (int it = 0; it < kAltIters; ++it) {
+    double A[8][9];
+    for (int i = 0; i < q; ++i) {
+      for (int j = 0; j < q; ++j) {
+        int64_t t = 0;
+        for (int64_t k = 0; k < g; ++k) t += (((code[k] >> i) ^ (code[k] >> j)) & 1) ? -1 : 1;
+        A[i][j] = (double)t;
+      }
+      double c = 0.0;
+      for (int64_t k = 0; k < g; ++k) c = c + (((code[k] >> i) & 1) ? w[k] : -w[k]);
+      A[i][q] = c;
+    }
+    double sol[8];
+    if (!solve_in_order(q, A, sol)) break;
+    int flip = 0;
+    for (int i = 0; i < q; ++i) {
+      a[i] = sol[i];
+      if (a[i] < 0.0) {
+        a[i] = -a[i];
+        flip |= 1 << i;
+      }
+    }
+    bool changed = false;
+    assign_codes(w, g, q, a, code_new.data());
+    for (int64_t k = 0; k < g; ++k) {
+      if (code_new[k] != (code[k] ^ flip)) changed = true;
+      code[k] = code_new[k];
+    }
+    if (!changed) break;
+  }
+  double stored[8];
+  for (int i = 0; i < q; ++i) {
+    a16[i] = double_to_half(a[i]);
+    stored[i] = (double)half_to_float(a16[i]);
+  }
+  assign_codes(w, g, q, stored, code.data());
+}
+
 }  // namespace
 
 extern "C" {
@@ -205,9 +309,10 @@ int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int 
   if (!W || !bits_out || !alpha_out) return LUTGEMM_EINVAL;
   if (!make_shape(m, n, q, g, &s)) return LUTGEMM_EINVAL;
   if (mu != 8) return LUTGEMM_EUNSUPPORTED;
-  if (mode != LUTGEMM_Q_GREEDY && mode != LUTGEMM_Q_GREEDY_MEAN_OFFSET && mode != LUTGEMM_Q_UNIFORM_RTN)
+  if (mode != LUTGEMM_Q_GREEDY && mode != LUTGEMM_Q_GREEDY_MEAN_OFFSET && mode != LUTGEMM_Q_UNIFORM_RTN &&
+      mode != LUTGEMM_Q_ALTERNATING)
     return LUTGEMM_EUNSUPPORTED;
-  const bool has_offset = mode != LUTGEMM_Q_GREEDY;
+  const bool has_offset = mode == LUTGEMM_Q_GREEDY_MEAN_OFFSET || mode == LUTGEMM_Q_UNIFORM_RTN;
   if (has_offset && !z_out) return LUTGEMM_EINVAL;
 
   uint8_t* bits = static_cast<uint8_t*>(bits_out);
@@ -219,7 +324,8 @@ int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int 
 
   parallel_blocks(s.RB, [&](int64_t rb0, int64_t rb1) {
     std::vector<float> res(G);
-    std::vector<int> code(G);
+    std::vector<int> code(G), code_new(G);
+    std::vector<double> w64(G), r64(G);
     for (int64_t r = rb0 * kRowsPerBlock; r < std::min<int64_t>(m, rb1 * kRowsPerBlock); ++r) {
       const int64_t rb = r / kRowsPerBlock, rho = r % kRowsPerBlock;
       for (int64_t gi = 0; gi < s.NG; ++gi) {
@@ -260,6 +366,21 @@ int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int 
             }
           }
           *z_dst = double_to_half((double)(zsum + lo));
+          continue;
+        }
+
+        if (mode == LUTGEMM_Q_ALTERNATING) {
+          uint16_t a16[8];
+          for (int64_t k = 0; k < G; ++k) w64[k] = (double)res[k];
+          alternating_group(w64.data(), G, q, code, code_new, r64, a16);
+          for (int i = 0; i < q; ++i) {
+            a_dst[i * 4] = a16[i];
+            for (int64_t c = 0; c < cpg; ++c) {
+              unsigned key = 0;
+              for (int j = 0; j < 8; ++j) key |= (unsigned)((code[c * 8 + j] >> i) & 1) << j;
+              bits[key_offset(s, slots[gi * cpg + c], i, r)] = (uint8_t)key;
+            }
+          }
           continue;
         }
 

@@ -13,7 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "liblutgemm.so")
 
 LUTGEMM_OK, LUTGEMM_EINVAL, LUTGEMM_EUNSUPPORTED, LUTGEMM_EWORKSPACE, LUTGEMM_EHIP = 0, -1, -2, -3, -4
-LUTGEMM_Q_GREEDY, LUTGEMM_Q_GREEDY_MEAN_OFFSET, LUTGEMM_Q_UNIFORM_RTN = 0, 1, 2
+LUTGEMM_Q_GREEDY, LUTGEMM_Q_GREEDY_MEAN_OFFSET, LUTGEMM_Q_UNIFORM_RTN, LUTGEMM_Q_ALTERNATING = 0, 1, 2, 3
 LUTGEMM_Y_F16, LUTGEMM_Y_F32, LUTGEMM_ALPHA_SHARED = 0, 1, 2
 
 _c = ctypes
@@ -124,7 +124,7 @@ def lutgemm_pack_bcq(W, q, g, mu=8, mode=LUTGEMM_Q_GREEDY):
         raise LutGemmError(LUTGEMM_EINVAL, "lutgemm_pack_bcq")
     bits = np.empty(nb, dtype=np.uint8)
     alpha = np.empty(na // 2, dtype=np.float16)
-    z = np.empty(nz // 2, dtype=np.float16) if mode != LUTGEMM_Q_GREEDY else None
+    z = np.empty(nz // 2, dtype=np.float16) if mode in (LUTGEMM_Q_GREEDY_MEAN_OFFSET, LUTGEMM_Q_UNIFORM_RTN) else None
     _check(lib().lutgemm_pack_bcq(W.ctypes.data, m, n, q, g, mu, mode, bits.ctypes.data, alpha.ctypes.data,
                                   _addr(z)), "lutgemm_pack_bcq")
     return bits, alpha, z

@@ -13,7 +13,8 @@ from gpu_util import Packed, check_parity, make_workspace, row_l1_bound, run
 
 pytestmark = pytest.mark.gpu
 
-MODES = {"greedy": L.LUTGEMM_Q_GREEDY, "greedy_z": L.LUTGEMM_Q_GREEDY_MEAN_OFFSET, "rtn": L.LUTGEMM_Q_UNIFORM_RTN}
+MODES = {"greedy": L.LUTGEMM_Q_GREEDY, "greedy_z": L.LUTGEMM_Q_GREEDY_MEAN_OFFSET, "rtn": L.LUTGEMM_Q_UNIFORM_RTN,
+         "alt": L.LUTGEMM_Q_ALTERNATING}
 
 
 def _oracle_full(p, x16):
@@ -43,6 +44,7 @@ CASES = [
     (515, 5120, 4, 128, "greedy"),
     (130, 1032, 5, 24, "greedy_z"),      # g % 16 != 0, second tile holds one chunk
     (96, 1048, 3, 8, "rtn"),             # ragged tile AND split groups
+    (200, 1024, 3, 128, "alt"),          # alternating BCQ scales (not ordered by plane)
 ]
 
 
