@@ -64,12 +64,7 @@ struct GemvParams {
   int batch;              // activation vectors
 };
 
-// DPP controls (GFX9 encoding)
-constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
-constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
-constexpr int kDppRowMirror = 0x140;     // lane i <- lane 15-i within a row of 16
-constexpr int kDppRowHalfMirror = 0x141; // lane i <- lane 7-i within 8
-
+// v under a DPP control (GFX9 encoding)
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
@@ -881,6 +876,7 @@ __global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
   finish_row_range<2>(p, lut, rs, rb0, rb1);
 }
 
+#include "lutgemm_quad.h"
 #include "lutgemm_planes_mfma.h"
 
 // Zero the arrival counters of a fresh workspace.
@@ -958,6 +954,37 @@ GemvKernel pick_pair_kernel(int q, bool has_z, bool shared, int64_t g) {
   return has_z ? pick_pair_mode<true, 0>(q, g) : pick_pair_mode<false, 0>(q, g);
 }
 
+template <bool HAS_Z, int AM2, int AM1>
+GemvKernel pick_quad_q(int q) {
+#ifdef LUT_ONLY_Q
+  return q == LUT_ONLY_Q ? lutgemm_quad_kernel<LUT_ONLY_Q, HAS_Z, AM2, AM1> : nullptr;
+#else
+  switch (q) {
+    case 1: return lutgemm_quad_kernel<1, HAS_Z, AM2, AM1>;
+    case 2: return lutgemm_quad_kernel<2, HAS_Z, AM2, AM1>;
+    case 3: return lutgemm_quad_kernel<3, HAS_Z, AM2, AM1>;
+    case 4: return lutgemm_quad_kernel<4, HAS_Z, AM2, AM1>;
+    case 5: return lutgemm_quad_kernel<5, HAS_Z, AM2, AM1>;
+    case 6: return lutgemm_quad_kernel<6, HAS_Z, AM2, AM1>;
+    case 7: return lutgemm_quad_kernel<7, HAS_Z, AM2, AM1>;
+    case 8: return lutgemm_quad_kernel<8, HAS_Z, AM2, AM1>;
+  }
+  return nullptr;
+#endif
+}
+
+template <bool HAS_Z, int SH>
+GemvKernel pick_quad_mode(int q, int64_t g) {   // a lane's dwords are chunks of one sub-slab, as in the pair kernel
+  if (g % 64 == 0) return pick_quad_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
+  if (g % 32 == 0) return pick_quad_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
+  return pick_quad_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
+}
+
+GemvKernel pick_quad_kernel(int q, bool has_z, bool shared, int64_t g) {
+  if (shared) return pick_quad_mode<true, kAlphaShared>(q, g);
+  return has_z ? pick_quad_mode<true, 0>(q, g) : pick_quad_mode<false, 0>(q, g);
+}
+
 int compute_units() {
   static int cached[64] = {0};
   int dev = 0;
@@ -1026,22 +1053,51 @@ void choose_pair_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
   }
 }
 
+// The same for the quad kernel: NT counts quarter ids, a unit is a pair of row blocks, the
+// final reduction runs for four vectors.
+void choose_quad_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
+  double best = 1e30;
+  const int pairs = (RB + 1) / 2;
+  const int max_rs = (pairs + kWaves - 1) / kWaves;
+  const int rows_per_pass = ((kWaves > 8) ? 3 : 8) * kThreads;
+  for (int tpg = 1; tpg <= NT && tpg <= 16; ++tpg) {
+    const int kg = (NT + tpg - 1) / tpg;
+    int rs = cus / kg;
+    rs = rs < 1 ? 1 : (rs > max_rs ? max_rs : rs);
+    const int units = (pairs + rs - 1) / rs;
+    const int rounds = (units + kWaves - 1) / kWaves;
+    const int tiles = (NT + kg - 1) / kg;
+    const int passes = (units * 32 + rows_per_pass - 1) / rows_per_pass;
+    const double cost = tiles * (rounds + 1.75) + 1.25 * 4 * passes * ((kg + 15) / 16);
+    if (cost < best) {
+      best = cost;
+      *KG = kg;
+      *TPG = tpg;
+      *RS = rs;
+    }
+  }
+}
+
 // choose_grid plus the tuning overrides (environment variables, for sweeps).
-void plan_grid(int cus, bool pair, const char* tpg_var, const char* rs_var, GemvParams* p) {
+// vectors: 1 (GEMV kernel), 2 (pair kernel), 4 (quad kernel)
+void plan_grid(int cus, int vectors, const char* tpg_var, const char* rs_var, GemvParams* p) {
   const int wgs = cus > 256 ? 256 : cus;
-  if (pair)
+  if (vectors == 4)
+    choose_quad_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
+  else if (vectors == 2)
     choose_pair_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
   else
     choose_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
   const int tpg = env_int(tpg_var), rs = env_int(rs_var);
-  const int max_rs = (p->RB + kWaves - 1) / kWaves;
+  const int row_units = vectors == 4 ? (p->RB + 1) / 2 : p->RB;
+  const int max_rs = (row_units + kWaves - 1) / kWaves;
   if (tpg > 0) {
     p->TPG = tpg > p->NT ? p->NT : tpg;
     p->KG = (p->NT + p->TPG - 1) / p->TPG;
     p->row_splits = wgs / p->KG;
     p->row_splits = p->row_splits < 1 ? 1 : (p->row_splits > max_rs ? max_rs : p->row_splits);
   }
-  if (rs > 0) p->row_splits = rs > 256 ? 256 : (rs > p->RB ? p->RB : rs);
+  if (rs > 0) p->row_splits = rs > 256 ? 256 : (rs > row_units ? row_units : rs);
 }
 
 constexpr size_t kCounterBytes = 32768;   // 32 activation vectors x 256 row ranges
@@ -1148,8 +1204,8 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.NG = (int)(n / gg);
   p.g = (int)gg;
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
-  plan_grid(cus, false, "LUTGEMM_TPG", "LUTGEMM_RS", &p);
-  const int64_t m_pad = (int64_t)p.RB * 16;
+  plan_grid(cus, 1, "LUTGEMM_TPG", "LUTGEMM_RS", &p);
+  const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
   p.kg_stride = m_pad * batch;
 
   GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg);
@@ -1162,28 +1218,36 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.vec_stride = m_pad;
   const size_t y_elem = p.y_f32 ? sizeof(float) : sizeof(__half);
 
-  // Activation vectors two at a time (one stream of the weights per pair), a last odd one alone.
-  GemvParams pp = p;   // grid of the pair kernel: half tiles instead of tiles
-  GemvKernel pair_kern = nullptr;
-  if (batch >= 2) {
+  // Activation vectors four at a time (one stream of the weights per four), then a pair, then
+  // a single one: 7 = 4 + 2 + 1.
+  GemvParams pq = p, pp = p;
+  GemvKernel quad_kern = nullptr, pair_kern = nullptr;
+  if (batch >= 4) {
+    pq.NT = 4 * p.NT;   // quarter ids; those a ragged last tile does not have are skipped by the kernel
+    plan_grid(cus, 4, "LUTGEMM_QUAD_TPG", "LUTGEMM_QUAD_RS", &pq);
+    quad_kern = pick_quad_kernel(q, z != nullptr, shared, gg);
+    if (!quad_kern) return LUTGEMM_EUNSUPPORTED;
+  }
+  if (batch % 4 >= 2) {
     const int last_chunks = p.nchunks - 128 * (p.NT - 1);
-    pp.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);
-    plan_grid(cus, true, "LUTGEMM_PAIR_TPG", "LUTGEMM_PAIR_RS", &pp);
+    pp.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);   // half tiles
+    plan_grid(cus, 2, "LUTGEMM_PAIR_TPG", "LUTGEMM_PAIR_RS", &pp);
     pair_kern = pick_pair_kernel(q, z != nullptr, shared, gg);
     if (!pair_kern) return LUTGEMM_EUNSUPPORTED;
   }
   for (int b = 0; b < batch;) {
-    const bool pair = b + 1 < batch;
-    GemvParams pb = pair ? pp : p;
+    const int take = batch - b >= 4 ? 4 : (batch - b >= 2 ? 2 : 1);
+    GemvParams pb = take == 4 ? pq : (take == 2 ? pp : p);
+    GemvKernel kb = take == 4 ? quad_kern : (take == 2 ? pair_kern : kern);
     pb.x = static_cast<const __half*>(x) + (int64_t)b * n;
     pb.partial = partials + (int64_t)b * m_pad;
     pb.counters = counters + (int64_t)b * 256;
     pb.y = static_cast<char*>(y) + (int64_t)b * m * y_elem;
     void* args[] = {&pb};
-    if (hipLaunchKernel(reinterpret_cast<const void*>(pair ? pair_kern : kern), dim3(pb.KG * pb.row_splits),
-                        dim3(kThreads), args, 0, stream) != hipSuccess)
+    if (hipLaunchKernel(reinterpret_cast<const void*>(kb), dim3(pb.KG * pb.row_splits), dim3(kThreads), args, 0,
+                        stream) != hipSuccess)
       return LUTGEMM_EHIP;
-    b += pair ? 2 : 1;
+    b += take;
   }
   return LUTGEMM_OK;
 }
@@ -1235,7 +1299,7 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
     }
   }
   if (p.row_splits > 256 && p.KG > 1) return LUTGEMM_EUNSUPPORTED;   // 256 arrival counters per call
-  const int64_t m_pad = (int64_t)p.RB * 16;
+  const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;
   p.kg_stride = m_pad * batch;
   p.vec_stride = m_pad;
   p.counters = static_cast<uint32_t*>(workspace);

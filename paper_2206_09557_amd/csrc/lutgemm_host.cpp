@@ -297,10 +297,12 @@ size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int b
   Shape s;
   if (mu != 8 || batch < 1 || batch > 32 || !make_shape(m, n, q, g, &s)) return 0;
   // arrival counters (32 KB), a spare area for results nobody reads (512 KB), then one fp32
-  // partial per (K group, activation vector, padded row); pairs of vectors split K over half
-  // tiles, so twice as many groups can occur
-  const size_t groups = (size_t)s.NT * (batch >= 2 ? 2 : 1);
-  return (size_t)32768 + (size_t)524288 + groups * batch * s.RB * kRowsPerBlock * sizeof(float);
+  // partial per (K group, activation vector, row of an even number of row blocks); four
+  // vectors at a time split K over quarter tiles, two over half tiles, so up to four (two)
+  // times as many groups as tiles can occur
+  const size_t groups = (size_t)s.NT * (batch >= 4 ? 4 : (batch >= 2 ? 2 : 1));
+  const size_t rows = (size_t)(s.RB + (s.RB & 1)) * kRowsPerBlock;
+  return (size_t)32768 + (size_t)524288 + groups * batch * rows * sizeof(float);
 }
 
 int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int mu, int mode,
