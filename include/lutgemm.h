@@ -185,13 +185,13 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* As lutgemm_gemv for `batch` activation vectors (1 <= batch <= 32): x is fp16
-   [batch][n], y is [batch][m], workspace sized for this batch.  The vectors are taken two
-   at a time: one table set per activation vector, each fetched key looked up in both, so
-   the weights are streamed once per pair (the small-batch case discussed in section 6);
-   an odd last vector runs as a lutgemm_gemv.  Row v of y equals, bit for bit, what the
-   same call would give for any other batch that places vector v at an index of the same
-   parity role (paired or last-odd); it is within the documented tolerance of, but not
-   bitwise equal to, the lutgemm_gemv result.                                            */
+   [batch][n], y is [batch][m], workspace sized for this batch.  The vectors are taken four
+   at a time, then two, then one (7 = 4 + 2 + 1): one table set per activation vector, each
+   fetched key looked up in all of them with one LDS read, so the weights are streamed once
+   per four vectors (the small-batch case discussed in section 6).  A vector's result does
+   not depend on the other vectors of the call, only on whether it is processed in a group
+   of four, two or one; between those three it agrees to the documented tolerance, not bit
+   for bit.  Bitwise reproducible from run to run.                                       */
 int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void* z, void* y,
                  int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -202,7 +202,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
    scale per group (section 3.2: y = sum_i A_i o (B_i . x); offset term of eq. 3).  Its
    time does not grow with batch up to 16 vectors, where the lookup path's does (the
    limitation discussed in section 6), so it is the faster of the two from a batch of
-   about three.  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
+   about eight.  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
    included when n % 64 == 0): LUTGEMM_EUNSUPPORTED otherwise, as is
    LUTGEMM_ALPHA_SHARED.  Bitwise reproducible.                                          */
 int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
