@@ -281,3 +281,31 @@ def test_random_shapes_all_paths(m, n, q, g, mode, batch):
     if mode == "rtn":                      # shared-scale layout: bitwise the same as per-plane scales
         p.share()
         np.testing.assert_array_equal(run(p, x, f32_out=True, shared=True), y)
+
+
+@pytest.mark.parametrize("m,n,q,g,batch", [
+    (16, 262144, 2, 128, None),     # one row block, 256 K tiles: deep split-K
+    (40, 65536, 3, 1024, 4),        # few rows, long rows, four vectors
+    (200000, 64, 2, 64, None),      # many rows, a single ragged K tile of 8 chunks
+    (70001, 128, 3, 0, 6),          # odd number of row blocks, row-wise scales, 4 + 2 vectors
+])
+def test_extreme_aspect_ratios(m, n, q, g, batch):
+    print(f"case extreme m={m} n={n} q={q} g={g} batch={batch}", flush=True)
+    W = synth.weights_fp16(m, n, seed=9000 + q)
+    x = synth.activations_fp16(n, seed=9500 + q, batch=batch)
+    p = Packed.from_weights(W, q, g)
+    del W
+    rows = np.unique(np.concatenate([np.arange(min(m, 40)), np.arange(max(0, m - 40), m),
+                                     np.random.default_rng(9).integers(0, m, size=60)]))
+    a = O.decode_alpha(p.alpha, m, 1 if g == 0 else n // g, q)
+    bound = row_l1_bound(a, None, n if g == 0 else g)
+    y = run(p, x, f32_out=True)
+    xs = x if batch else x[None, :]
+    ys = y if batch else y[None, :]
+    yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, xs, m, n, q, g, rows=rows)
+    for b in range(xs.shape[0]):
+        check_parity(ys[b][rows], yref[b], xs[b], bound[rows], f32_out=True)
+    if (n if g == 0 else g) % 64 == 0:
+        ym = run(p, xs, f32_out=True, mfma=True)
+        for b in range(xs.shape[0]):
+            check_parity(ym[b][rows], yref[b], xs[b], bound[rows], f32_out=True)
