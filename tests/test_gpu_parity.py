@@ -309,3 +309,46 @@ def test_extreme_aspect_ratios(m, n, q, g, batch):
         ym = run(p, xs, f32_out=True, mfma=True)
         for b in range(xs.shape[0]):
             check_parity(ym[b][rows], yref[b], xs[b], bound[rows], f32_out=True)
+
+
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    # serving loops replay captured work: the entry points enqueue kernels only (no allocation,
+    # no synchronisation, counters reset by the kernels themselves), so a captured call must
+    # give the eager result on every replay, also after the inputs have changed in place
+    import torch
+    m, n, q, g, batch = 1500, 3072, 3, 128, 7          # 4 + 2 + 1 vectors: all three lookup kernels
+    W = synth.weights_fp16(m, n, seed=9900)
+    p = Packed.from_weights(W, q, g)
+    wsb = L.lutgemm_workspace_bytes(m, n, q, g, 8, batch)
+    ws = make_workspace(wsb)
+    d_x = torch.zeros((batch, n), dtype=torch.float16, device="cuda")
+    d_y = torch.zeros((batch, m), dtype=torch.float32, device="cuda")
+    d_y1 = torch.zeros(m, dtype=torch.float32, device="cuda")
+    d_ym = torch.zeros((batch, m), dtype=torch.float32, device="cuda")
+    ws2, ws3 = make_workspace(wsb), make_workspace(wsb)
+
+    def enqueue(stream):
+        L.lutgemm_gemm(d_x, p.d_bits, p.d_alpha, None, d_y, q, g, 8, m, n, batch, L.LUTGEMM_Y_F32, ws, wsb, stream)
+        L.lutgemm_gemv(d_x, p.d_bits, p.d_alpha, None, d_y1, q, g, 8, m, n, L.LUTGEMM_Y_F32, ws2, wsb, stream)
+        L.lutgemm_gemm_mfma(d_x, p.d_bits, p.d_alpha, None, d_ym, q, g, 8, m, n, batch, L.LUTGEMM_Y_F32, ws3, wsb, stream)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        enqueue(side.cuda_stream)                       # warm-up outside the capture
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x = synth.activations_fp16(n, seed=9910 + rep, batch=batch)
+        d_x.copy_(torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16))
+        d_y.fill_(float("nan")); d_y1.fill_(float("nan")); d_ym.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got1, gotm = d_y.cpu().numpy(), d_y1.cpu().numpy(), d_ym.cpu().numpy()
+        np.testing.assert_array_equal(got, run(p, x, f32_out=True))
+        np.testing.assert_array_equal(got1, run(p, x[0], f32_out=True))
+        np.testing.assert_array_equal(gotm, run(p, x, f32_out=True, mfma=True))
