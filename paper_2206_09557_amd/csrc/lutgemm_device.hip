@@ -54,7 +54,9 @@ struct GemvParams {
   int nchunks;            // n / 8
   int KG;                 // K groups (workgroups along K)
   int TPG;                // K tiles per K group
-  int row_splits;         // workgroups along the rows
+  int row_splits;         // workgroups along the rows (grid y; K groups are grid x)
+  int range_base;         // row units (row blocks; pairs of them in the quad kernel) per row range ...
+  int range_rem;          // ... plus one for the first range_rem ranges
   int y_f32;              // output type
   // pair kernel only
   int n;                  // columns
@@ -63,6 +65,14 @@ struct GemvParams {
   // matrix-core kernel only
   int batch;              // activation vectors
 };
+
+// Row range of this workgroup in row units: ranges differ by at most one unit.  (Grid x =
+// K group, grid y = row range: no division anywhere in the kernel preamble.)
+__device__ __forceinline__ void row_range(const GemvParams& p, int* u0, int* u1) {
+  const int rs = blockIdx.y;
+  *u0 = rs * p.range_base + min(rs, p.range_rem);
+  *u1 = *u0 + p.range_base + (rs < p.range_rem ? 1 : 0);
+}
 
 // v under a DPP control (GFX9 encoding)
 template <int CTRL>
@@ -557,10 +567,10 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
   __shared__ float lut[kLutBytes / 4 + 4];
   // The lookup addresses are formed as if the tables start at LDS address 0.
   if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
-  const int kg = blockIdx.x % p.KG;
-  const int rs = blockIdx.x / p.KG;
-  const int rb0 = (int)((int64_t)p.RB * rs / p.row_splits);
-  const int rb1 = (int)((int64_t)p.RB * (rs + 1) / p.row_splits);
+  const int kg = blockIdx.x;
+  const int rs = blockIdx.y;
+  int rb0, rb1;
+  row_range(p, &rb0, &rb1);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
 
   for (int ti = 0; ti < p.TPG; ++ti) {
@@ -795,7 +805,7 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
     // same value).  The spare area has 128 bytes per wavefront: one spare line for all would
     // serialise every wavefront of the device on one memory channel.
     if (uid[0] >= n_units) return;
-    float* const spare0 = p.spare + ((blockIdx.x & 255) * 16 + wave) * 32;
+    float* const spare0 = p.spare + (((blockIdx.y * gridDim.x + blockIdx.x) & 255) * 16 + wave) * 32;
     constexpr int kHeld = kStoreLag > 0 ? kStoreLag : 1;
     float held0[kHeld], held1[kHeld];
     float* held_to[kHeld];     // wave-uniform; the second vector's result goes held_step further
@@ -858,10 +868,10 @@ template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
   __shared__ float lut[kLutBytes / 4 + 4];
   if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
-  const int kg = blockIdx.x % p.KG;
-  const int rs = blockIdx.x / p.KG;
-  const int rb0 = (int)((int64_t)p.RB * rs / p.row_splits);
-  const int rb1 = (int)((int64_t)p.RB * (rs + 1) / p.row_splits);
+  const int kg = blockIdx.x;
+  const int rs = blockIdx.y;
+  int rb0, rb1;
+  row_range(p, &rb0, &rb1);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
   for (int ti = 0; ti < p.TPG; ++ti) {
     const int h = kg * p.TPG + ti;
@@ -1243,8 +1253,11 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     pb.partial = partials + (int64_t)b * m_pad;
     pb.counters = counters + (int64_t)b * 256;
     pb.y = static_cast<char*>(y) + (int64_t)b * m * y_elem;
+    const int row_units = take == 4 ? (pb.RB + 1) / 2 : pb.RB;
+    pb.range_base = row_units / pb.row_splits;
+    pb.range_rem = row_units % pb.row_splits;
     void* args[] = {&pb};
-    if (hipLaunchKernel(reinterpret_cast<const void*>(kb), dim3(pb.KG * pb.row_splits), dim3(kThreads), args, 0,
+    if (hipLaunchKernel(reinterpret_cast<const void*>(kb), dim3(pb.KG, pb.row_splits), dim3(kThreads), args, 0,
                         stream) != hipSuccess)
       return LUTGEMM_EHIP;
     b += take;
@@ -1307,8 +1320,11 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   p.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
   GemvKernel kern = pick_planes_kernel(q, z != nullptr, batch);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
+  if (p.row_splits > 65535) return LUTGEMM_EUNSUPPORTED;   // grid y
+  p.range_base = p.RB / p.row_splits;
+  p.range_rem = p.RB % p.row_splits;
   void* args[] = {&p};
-  if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.KG * p.row_splits), dim3(waves * 64), args, 0,
+  if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.KG, p.row_splits), dim3(waves * 64), args, 0,
                       static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return LUTGEMM_EHIP;
   return LUTGEMM_OK;

@@ -325,10 +325,10 @@ __global__ __launch_bounds__(PlanesCfg<Q>::kThreadsM) void lutgemm_planes_mfma_k
     sign[k] = e;
   }
 
-  const int kg = blockIdx.x % p.KG;
-  const int rs = blockIdx.x / p.KG;
-  const int rb0 = (int)((int64_t)p.RB * rs / p.row_splits);
-  const int rb1 = (int)((int64_t)p.RB * (rs + 1) / p.row_splits);
+  const int kg = blockIdx.x;
+  const int rs = blockIdx.y;
+  int rb0, rb1;
+  row_range(p, &rb0, &rb1);
   const int kt0 = kg * p.TPG;
   const int kt1 = min(kt0 + p.TPG, p.NT);
 

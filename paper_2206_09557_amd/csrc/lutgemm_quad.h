@@ -202,7 +202,7 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
     // bottom, results stored one unit later right after a fetch, surplus passes store to the
     // wavefront's spare 128 bytes (all four vectors onto the same 32 floats).
     if (uid[0] >= n_units) return;
-    float* const spare0 = p.spare + ((blockIdx.x & 255) * 16 + wave) * 32;
+    float* const spare0 = p.spare + (((blockIdx.y * gridDim.x + blockIdx.x) & 255) * 16 + wave) * 32;
     float held[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     float* held_to = spare0;       // wave-uniform; vector v goes v * held_step further
     int64_t held_step = 0;
@@ -257,11 +257,12 @@ template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_quad_kernel(GemvParams p) {
   __shared__ float lut[kLutBytes / 4 + 4];
   if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
-  const int kg = blockIdx.x % p.KG;
-  const int rs = blockIdx.x / p.KG;
-  const int pairs = (p.RB + 1) >> 1;
-  const int rb0 = 2 * (int)((int64_t)pairs * rs / p.row_splits);
-  const int rb1 = min(2 * (int)((int64_t)pairs * (rs + 1) / p.row_splits), p.RB);
+  const int kg = blockIdx.x;
+  const int rs = blockIdx.y;
+  int pair0, pair1;                 // row units are pairs of row blocks here
+  row_range(p, &pair0, &pair1);
+  const int rb0 = 2 * pair0;
+  const int rb1 = min(2 * pair1, p.RB);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
   bool first = true;
   for (int ti = 0; ti < p.TPG; ++ti) {
