@@ -58,6 +58,7 @@ struct GemvParams {
   int range_base;         // row units (row blocks; pairs of them in the quad kernel) per row range ...
   int range_rem;          // ... plus one for the first range_rem ranges
   int y_f32;              // output type
+  int g_shift;            // log2(g / 8) when g is a power of two, else -1
   // pair kernel only
   int n;                  // columns
   int64_t vec_stride;     // floats between the partials of the two vectors of a pair
@@ -72,6 +73,11 @@ __device__ __forceinline__ void row_range(const GemvParams& p, int* u0, int* u1)
   const int rs = blockIdx.y;
   *u0 = rs * p.range_base + min(rs, p.range_rem);
   *u1 = *u0 + p.range_base + (rs < p.range_rem ? 1 : 0);
+}
+
+// Group of a chunk (8 columns): chunk / (g / 8), a shift for the usual power-of-two group sizes.
+__device__ __forceinline__ int group_of_chunk(const GemvParams& p, int chunk) {
+  return p.g_shift >= 0 ? (chunk >> p.g_shift) : (chunk * 8) / p.g;
 }
 
 // v under a DPP control (GFX9 encoding)
@@ -174,7 +180,7 @@ struct Unit {
 };
 
 // Group index of every (dword, sub-slab) of this lane in tile kt.
-template <int T>
+template <int T, bool SHIFT = true>
 __device__ __forceinline__ void lane_groups(const GemvParams& p, int kt, int lane, int chunks_in_tile, int (&grp)[4][T]) {
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
@@ -182,7 +188,7 @@ __device__ __forceinline__ void lane_groups(const GemvParams& p, int kt, int lan
 #pragma unroll
     for (int t = 0; t < T; ++t) {
       const int cc = min(T * slot + t, chunks_in_tile - 1);
-      grp[s][t] = ((128 * kt + cc) * 8) / p.g;
+      grp[s][t] = SHIFT ? group_of_chunk(p, 128 * kt + cc) : ((128 * kt + cc) * 8) / p.g;
     }
   }
 }
@@ -405,7 +411,8 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   const int64_t tile_base = (int64_t)kt * p.RB * Q * 2048;
 
   int grp[4][T];
-  lane_groups<T>(p, kt, lane, chunks_in_tile, grp);
+  // (the per-chunk scale mode has no registers to spare for the two code paths of the shift)
+  lane_groups<T, (AMODE & 3) != kAlphaPerChunk>(p, kt, lane, chunks_in_tile, grp);
   // the row of the 16-row block whose sum this lane ends up with (see quad_rows_reduce)
   const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
 
@@ -705,7 +712,7 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const int slot = (lane & ~3) | ((s + lane) & 3);
-    grp[s][0] = ((128 * kt + min(tile_T * slot + t0, chunks_in_tile - 1)) * 8) / p.g;
+    grp[s][0] = group_of_chunk(p, 128 * kt + min(tile_T * slot + t0, chunks_in_tile - 1));
   }
 
   // ---- activations of this lane's slot, both vectors (fetched before anything else) ----
@@ -1213,6 +1220,9 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.NT = (p.nchunks + 127) / 128;
   p.NG = (int)(n / gg);
   p.g = (int)gg;
+  p.g_shift = -1;
+  for (int sh = 0; sh < 31; ++sh)
+    if ((gg >> 3) == ((int64_t)1 << sh)) p.g_shift = sh;
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
   plan_grid(cus, 1, "LUTGEMM_TPG", "LUTGEMM_RS", &p);
   const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
@@ -1297,6 +1307,9 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   p.NT = (p.nchunks + 127) / 128;
   p.NG = (int)(n / gg);
   p.g = (int)gg;
+  p.g_shift = -1;
+  for (int sh = 0; sh < 31; ++sh)
+    if ((gg >> 3) == ((int64_t)1 << sh)) p.g_shift = sh;
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
   const int waves = q > 4 ? 4 : 8;
   plan_planes_grid(cus, waves, batch, &p);

@@ -110,7 +110,7 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const int L = (lq & ~3) | ((s + lq) & 3);
-    grp[s][0] = ((128 * kt + min(tile_T * (32 * h + L) + t0, chunks_in_tile - 1)) * 8) / p.g;
+    grp[s][0] = group_of_chunk(p, 128 * kt + min(tile_T * (32 * h + L) + t0, chunks_in_tile - 1));
   }
 
   // ---- activations: wavefront id b (of 16) builds key range 32 * (b % 8) of vectors
