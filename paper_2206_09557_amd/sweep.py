@@ -5,8 +5,8 @@ batch-1 latency follows the memory footprint of eq. 4, and a small group size ra
 
 The kernel is data-oblivious, so the packed buffers are filled with random key bytes and
 random positive fp16 scales directly on the device (no quantiser run): sizes, layouts and
-access pattern are those of a packed layer.  Several copies of every configuration rotate so
-that the 256 MB Infinity Cache does not serve the weights.  Prints a markdown table.
+access pattern are those of a packed layer.  Copies of every configuration worth about 1 GB
+rotate, so that neither the L2 nor the 256 MB Infinity Cache serves the weights.  Prints a markdown table.
 """
 from __future__ import annotations
 
@@ -21,6 +21,9 @@ def main(argv=None):
     ap.add_argument("--iters", type=int, default=50)
     ap.add_argument("--q", type=str, default="1,2,3,4,5,6,7,8")
     ap.add_argument("--g", type=str, default="32,64,128,256,0")
+    ap.add_argument("--preset", choices=["none", "workloads"], default="none",
+                    help="workloads: every layer of the workload list (1024^2; OPT-13B q=4; OPT-175B q=3; LLaMA-65B "
+                         "q in 2..4 x g in 32, 64, 128, row-wise with offsets) instead of one shape")
     ap.add_argument("--layout", choices=["planes", "planes_z", "shared"], default="planes",
                     help="planes: q scales per group (eq. 4); planes_z: plus one offset per group; "
                          "shared: one scale and one offset per group (uniformly quantised weights, appendix C)")
@@ -34,18 +37,28 @@ def main(argv=None):
         print("sweep: no GPU visible", file=sys.stderr)
         return 2
     L.lib()
-    m, n = args.m, args.n
     stream = torch.cuda.current_stream().cuda_stream
     gen = torch.Generator(device="cuda").manual_seed(1234)
-    x = torch.randn(n, device="cuda", generator=gen).half()
-    y = torch.empty(m, dtype=torch.float16, device="cuda")
     rows = []
-    for q in [int(v) for v in args.q.split(",")]:
-        for g in [int(v) for v in args.g.split(",")]:
+    if args.preset == "workloads":
+        from . import synth
+        cases = [("1024^2", 1024, 1024, 3, 128, "planes")]
+        cases += [(f"OPT-13B {k}", *synth.OPT_13B[k], 4, 128, "planes") for k in ("qkv", "out", "fc1", "fc2")]
+        cases += [(f"OPT-175B {k}", *synth.OPT_175B[k], 3, 128, "planes") for k in ("qkv", "out", "fc1", "fc2")]
+        cases += [(f"LLaMA-65B {k}", *synth.LLAMA_65B[k], q, g, "planes_z")
+                  for k in ("qkv", "out", "gate_up", "down") for q in (2, 3, 4) for g in (32, 64, 128, 0)]
+    else:
+        cases = [("", args.m, args.n, q, g, args.layout) for q in [int(v) for v in args.q.split(",")]
+                 for g in [int(v) for v in args.g.split(",")]]
+    for name, m, n, q, g, layout in cases:
+        if True:
+            x = torch.randn(n, device="cuda", generator=gen).half()
+            y = torch.empty(m, dtype=torch.float16, device="cuda")
+            args.layout = layout
             nb = L.lutgemm_bits_bytes(m, n, q)
             na = L.lutgemm_alpha_shared_bytes(m, n, g) if args.layout == "shared" else L.lutgemm_alpha_bytes(m, n, q, g)
             nz = 0 if args.layout == "planes" else L.lutgemm_z_bytes(m, n, g)
-            copies = max(2, min(8, int(1.2e9 // (nb + na + nz)) or 2))
+            copies = max(2, min(80, -(-int(1.0e9) // (nb + na + nz))))   # about 1 GB in rotation: nothing stays cached
             bits = [torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=gen) for _ in range(copies)]
             alpha = [(torch.rand(na // 2, device="cuda", generator=gen) * 0.05 + 0.001).half() for _ in range(copies)]
             zs = [None] * copies if nz == 0 else [(torch.rand(nz // 2, device="cuda", generator=gen) * 0.02 - 0.01).half()
@@ -70,14 +83,21 @@ def main(argv=None):
             us = a.elapsed_time(b) * 1e3 / args.iters
             gg = n if g == 0 else g
             footprint = m * n * q // 8 + na + nz                    # bits + scales (+ offsets), bytes
-            rows.append((q, g, footprint, us))
+            rows.append((name, m, n, layout, q, g, footprint, us))
             del bits, alpha, zs, ws
-            print(f"[sweep] q={q} g={g or 'row'}: {us:.2f} us", file=sys.stderr, flush=True)
-    print(f"layout: {args.layout}, m = {m}, n = {n}")
+            print(f"[sweep] {name} {m}x{n} q={q} g={g or 'row'}: {us:.2f} us", file=sys.stderr, flush=True)
+    if args.preset == "workloads":
+        print("| layer | m x n | q | g | offsets | footprint MB | us / GEMV | GB/s | % of 8 TB/s |")
+        print("|---|---|---|---|---|---|---|---|---|")
+        for name, m, n, layout, q, g, fp, us in rows:
+            print(f"| {name} | {m} x {n} | {q} | {g or 'row'} | {'yes' if layout != 'planes' else 'no'} | {fp / 1e6:.2f} | "
+                  f"{us:.2f} | {fp / us / 1e3:.0f} | {fp / us / 1e3 / 80:.1f} |")
+        return 0
+    print(f"layout: {rows[0][3]}, m = {rows[0][1]}, n = {rows[0][2]}")
     print()
     print(f"| q | g | footprint MB | us / GEMV | GB/s | us per MB |")
     print("|---|---|---|---|---|---|")
-    for q, g, fp, us in rows:
+    for _, _, _, _, q, g, fp, us in rows:
         print(f"| {q} | {g or 'row'} | {fp / 1e6:.2f} | {us:.2f} | {fp / us / 1e3:.0f} | {us / (fp / 1e6):.3f} |")
     return 0
 
