@@ -165,6 +165,9 @@ __device__ __forceinline__ float quad_rows_reduce(const float (&acc)[4], int lan
 // group), alpha_0, and that plane i has the scale 2^i * alpha_0 (appendix C: the scales of
 // uniformly quantised weights): one fetch of four rows instead of four rows x q planes.
 enum { kAlphaQuad = 0, kAlphaPerSlot = 1, kAlphaPerChunk = 2, kAlphaShared = 4 };
+// Also carried in the mode: fetch a wavefront's first unit before the tables are built (GEMV
+// kernel, short row ranges: see tile_body).
+enum { kEarlyFirst = 8 };
 
 // What one wavefront fetches for planes I0 .. I0+QP-1 of one (K tile, row block) unit of a
 // Q-plane layer.  (Layers of up to four planes are fetched whole; more planes go in two
@@ -453,7 +456,13 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   if (threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = kWaves;   // units 0..kWaves-1 are taken
   U u[kDepth + 1];
   int cur = wave;                               // unit being computed (or about to be)
-  if (kDepth == 1) load_unit(u[0], p, tile_base, rb0 + min(cur, u_clamp), lane, grp, partial, out_row, !first_tile);
+  // kEarlyFirst (chosen by the host for short row ranges, one to three units per wavefront):
+  // the first unit is fetched before the tables are built, so that its latency and that of
+  // the activations overlap.  On long ranges this does not pay: every wavefront of the
+  // device then floods the memory system at once and the activations queue behind.
+  constexpr bool kEarly = kDepth == 0 && (AMODE & kEarlyFirst) != 0;
+  if (kDepth == 1 || kEarly)
+    load_unit(u[0], p, tile_base, rb0 + min(cur, u_clamp), lane, grp, partial, out_row, !first_tile);
 
   build_tile_tables<T>(lut, chunks_in_tile, wave, lane, xraw);
   uint32_t lane_base[4];
@@ -475,7 +484,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
       if (kDepth == 1) {
         nxt = next_unit(lut, lane);
         load_unit(u[(j + 1) & 1], p, tile_base, rb0 + min(nxt, u_clamp), lane, grp, partial, out_row, !first_tile);
-      } else {
+      } else if (!kEarly) {
         load_unit(u[0], p, tile_base, rb0 + cur, lane, grp, partial, out_row, !first_tile);
       }
       int row_in_block;
@@ -486,6 +495,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
       n_parked = j + 1;
       cur = (kDepth == 1) ? nxt : next_unit(lut, lane);
       if (cur >= n_units) break;
+      if (kEarly) load_unit(u[0], p, tile_base, rb0 + cur, lane, grp, partial, out_row, !first_tile);   // no fetch in flight at the exit above
     }
     if (lane_row < n_parked) store_device_coherent(partial + parked_rb * 16 + out_row, parked);
   }
@@ -924,7 +934,9 @@ GemvKernel pick_q(int q) {
 }
 
 template <bool HAS_Z, int SH>
-GemvKernel pick_mode(int q, int64_t g) {
+GemvKernel pick_mode(int q, int64_t g, bool early) {
+  if (g % 64 == 0 && early && SH == 0 && q <= 4)   // the early first fetch exists for the common case only
+    return pick_q<HAS_Z, kAlphaQuad | kEarlyFirst, kAlphaQuad | kEarlyFirst>(q);
   if (g % 64 == 0) return pick_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
   if (g % 32 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
   if (g % 16 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
@@ -932,9 +944,9 @@ GemvKernel pick_mode(int q, int64_t g) {
 }
 
 // shared: the scale buffer is in the shared-scale layout (offsets are then always present)
-GemvKernel pick_kernel(int q, bool has_z, bool shared, int64_t g) {
-  if (shared) return pick_mode<true, kAlphaShared>(q, g);
-  return has_z ? pick_mode<true, 0>(q, g) : pick_mode<false, 0>(q, g);
+GemvKernel pick_kernel(int q, bool has_z, bool shared, int64_t g, bool early) {
+  if (shared) return pick_mode<true, kAlphaShared>(q, g, early);
+  return has_z ? pick_mode<true, 0>(q, g, early) : pick_mode<false, 0>(q, g, early);
 }
 
 // Pair kernel: a lane's dword is one chunk, so the per-chunk scale mode does not occur.
@@ -1228,7 +1240,11 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
   p.kg_stride = m_pad * batch;
 
-  GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg);
+  // short row ranges (few units per wavefront): fetch the first unit before the tables are built
+  const int early_env = env_int("LUTGEMM_EARLY_MAX");   // tuning override: rounds of units per wavefront, negative = never
+  const int early_max = early_env == 0 ? 3 : (early_env < 0 ? 0 : early_env);
+  const bool early = (p.RB + p.row_splits - 1) / p.row_splits <= early_max * kWaves;
+  GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg, early);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
 
   uint32_t* counters = static_cast<uint32_t*>(workspace);
