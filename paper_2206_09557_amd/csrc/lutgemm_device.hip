@@ -456,7 +456,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   if (threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = kWaves;   // units 0..kWaves-1 are taken
   U u[kDepth + 1];
   int cur = wave;                               // unit being computed (or about to be)
-  // kEarlyFirst (chosen by the host for short row ranges, one to three units per wavefront):
+  // kEarlyFirst (chosen by the host for short row ranges, one or two units per wavefront):
   // the first unit is fetched before the tables are built, so that its latency and that of
   // the activations overlap.  On long ranges this does not pay: every wavefront of the
   // device then floods the memory system at once and the activations queue behind.
@@ -1242,7 +1242,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
 
   // short row ranges (few units per wavefront): fetch the first unit before the tables are built
   const int early_env = env_int("LUTGEMM_EARLY_MAX");   // tuning override: rounds of units per wavefront, negative = never
-  const int early_max = early_env == 0 ? 3 : (early_env < 0 ? 0 : early_env);
+  const int early_max = early_env == 0 ? 2 : (early_env < 0 ? 0 : early_env);
   const bool early = (p.RB + p.row_splits - 1) / p.row_splits <= early_max * kWaves;
   GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg, early);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
