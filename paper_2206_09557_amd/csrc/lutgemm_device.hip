@@ -1028,9 +1028,31 @@ int compute_units() {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int env_int(const char* name) {
-  const char* v = getenv(name);
-  return v ? atoi(v) : 0;
+// Tuning overrides for sweeps (environment variables, read once per process; 0 = unset):
+// LUTGEMM_TPG / LUTGEMM_RS, LUTGEMM_PAIR_TPG / _RS, LUTGEMM_QUAD_TPG / _RS (K tiles per group,
+// row ranges of the three lookup kernels), LUTGEMM_MFMA_TPG, LUTGEMM_EARLY_MAX.
+struct Tuning {
+  int tpg[3], rs[3];   // by kernel: GEMV, pair, quad
+  int mfma_tpg, early_max;
+};
+const Tuning& tuning() {
+  static const Tuning t = [] {
+    auto env = [](const char* name) {
+      const char* v = getenv(name);
+      return v ? atoi(v) : 0;
+    };
+    Tuning r;
+    r.tpg[0] = env("LUTGEMM_TPG");
+    r.rs[0] = env("LUTGEMM_RS");
+    r.tpg[1] = env("LUTGEMM_PAIR_TPG");
+    r.rs[1] = env("LUTGEMM_PAIR_RS");
+    r.tpg[2] = env("LUTGEMM_QUAD_TPG");
+    r.rs[2] = env("LUTGEMM_QUAD_RS");
+    r.mfma_tpg = env("LUTGEMM_MFMA_TPG");
+    r.early_max = env("LUTGEMM_EARLY_MAX");
+    return r;
+  }();
+  return t;
 }
 
 // Workgroup grid: KG groups of TPG consecutive K tiles times row_splits row ranges, one
@@ -1107,9 +1129,9 @@ void choose_quad_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
   }
 }
 
-// choose_grid plus the tuning overrides (environment variables, for sweeps).
+// choose_grid plus the tuning overrides.
 // vectors: 1 (GEMV kernel), 2 (pair kernel), 4 (quad kernel)
-void plan_grid(int cus, int vectors, const char* tpg_var, const char* rs_var, GemvParams* p) {
+void plan_grid(int cus, int vectors, GemvParams* p) {
   const int wgs = cus > 256 ? 256 : cus;
   if (vectors == 4)
     choose_quad_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
@@ -1117,7 +1139,8 @@ void plan_grid(int cus, int vectors, const char* tpg_var, const char* rs_var, Ge
     choose_pair_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
   else
     choose_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
-  const int tpg = env_int(tpg_var), rs = env_int(rs_var);
+  const int which = vectors == 4 ? 2 : (vectors == 2 ? 1 : 0);
+  const int tpg = tuning().tpg[which], rs = tuning().rs[which];
   const int row_units = vectors == 4 ? (p->RB + 1) / 2 : p->RB;
   const int max_rs = (row_units + kWaves - 1) / kWaves;
   if (tpg > 0) {
@@ -1236,12 +1259,12 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   for (int sh = 0; sh < 31; ++sh)
     if ((gg >> 3) == ((int64_t)1 << sh)) p.g_shift = sh;
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
-  plan_grid(cus, 1, "LUTGEMM_TPG", "LUTGEMM_RS", &p);
+  plan_grid(cus, 1, &p);
   const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
   p.kg_stride = m_pad * batch;
 
   // short row ranges (few units per wavefront): fetch the first unit before the tables are built
-  const int early_env = env_int("LUTGEMM_EARLY_MAX");   // tuning override: rounds of units per wavefront, negative = never
+  const int early_env = tuning().early_max;   // tuning override: rounds of units per wavefront, negative = never
   const int early_max = early_env == 0 ? 2 : (early_env < 0 ? 0 : early_env);
   const bool early = (p.RB + p.row_splits - 1) / p.row_splits <= early_max * kWaves;
   GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg, early);
@@ -1260,14 +1283,14 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   GemvKernel quad_kern = nullptr, pair_kern = nullptr;
   if (batch >= 4) {
     pq.NT = 4 * p.NT;   // quarter ids; those a ragged last tile does not have are skipped by the kernel
-    plan_grid(cus, 4, "LUTGEMM_QUAD_TPG", "LUTGEMM_QUAD_RS", &pq);
+    plan_grid(cus, 4, &pq);
     quad_kern = pick_quad_kernel(q, z != nullptr, shared, gg);
     if (!quad_kern) return LUTGEMM_EUNSUPPORTED;
   }
   if (batch % 4 >= 2) {
     const int last_chunks = p.nchunks - 128 * (p.NT - 1);
     pp.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);   // half tiles
-    plan_grid(cus, 2, "LUTGEMM_PAIR_TPG", "LUTGEMM_PAIR_RS", &pp);
+    plan_grid(cus, 2, &pp);
     pair_kern = pick_pair_kernel(q, z != nullptr, shared, gg);
     if (!pair_kern) return LUTGEMM_EUNSUPPORTED;
   }
@@ -1330,7 +1353,7 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   const int waves = q > 4 ? 4 : 8;
   plan_planes_grid(cus, waves, batch, &p);
   {
-    const int tpg = env_int("LUTGEMM_MFMA_TPG");
+    const int tpg = tuning().mfma_tpg;
     if (tpg > 0) {
       const int min_rs = (p.RB + kPlanesMaxUnits * waves - 1) / (kPlanesMaxUnits * waves);
       p.TPG = tpg > p.NT ? p.NT : tpg;
