@@ -186,12 +186,13 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
 
 /* As lutgemm_gemv for `batch` activation vectors (1 <= batch <= 32): x is fp16
    [batch][n], y is [batch][m], workspace sized for this batch.  The vectors are taken four
-   at a time, then two, then one (7 = 4 + 2 + 1): one table set per activation vector, each
-   fetched key looked up in all of them with one LDS read, so the weights are streamed once
-   per four vectors (the small-batch case discussed in section 6).  A vector's result does
-   not depend on the other vectors of the call, only on whether it is processed in a group
-   of four, two or one; between those three it agrees to the documented tolerance, not bit
-   for bit.  Bitwise reproducible from run to run.                                       */
+   at a time; two or one left over have kernels of their own, three left over run as four
+   (the fourth table set repeats the third vector, its results are dropped).  One table set
+   per activation vector, each fetched key looked up in all of them with one LDS read, so
+   the weights are streamed once per four vectors (the small-batch case discussed in
+   section 6).  A vector's result does not depend on the other vectors of the call, only on
+   whether it is processed in a group of four, two or one; between those three it agrees
+   to the documented tolerance, not bit for bit.  Bitwise reproducible from run to run.                                       */
 int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void* z, void* y,
                  int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                  void* workspace, size_t workspace_bytes, void* hip_stream);

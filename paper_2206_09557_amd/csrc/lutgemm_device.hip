@@ -63,8 +63,8 @@ struct GemvParams {
   int n;                  // columns
   int64_t vec_stride;     // floats between the partials of the two vectors of a pair
   float* spare;           // [256 workgroup slots][16 wavefronts][2][16]: where results nobody reads are stored
-  // matrix-core kernel only
-  int batch;              // activation vectors
+  // matrix-core kernel: activation vectors; quad kernel: live vectors of this launch (3 or 4)
+  int batch;
 };
 
 // Row range of this workgroup in row units: ranges differ by at most one unit.  (Grid x =
@@ -525,6 +525,7 @@ __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut
   const int row_end = min(rb1 * 16, p.m);
 #pragma unroll
   for (int vec = 0; vec < NVEC; ++vec) {
+    if (NVEC == 4 && vec >= p.batch) continue;   // a quad launched for three vectors: nothing to write for the fourth
     const float* part = NVEC == 1 ? p.partial : p.partial + (int64_t)vec * p.vec_stride;
     for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
       const float* src[kRowsPerPass];
@@ -1261,7 +1262,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
   plan_grid(cus, 1, &p);
   const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
-  p.kg_stride = m_pad * batch;
+  p.kg_stride = m_pad * (batch + (batch % 4 == 3 ? 1 : 0));   // room for the dropped fourth vector of a quad of three
 
   // short row ranges (few units per wavefront): fetch the first unit before the tables are built
   const int early_env = tuning().early_max;   // tuning override: rounds of units per wavefront, negative = never
@@ -1277,17 +1278,18 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.vec_stride = m_pad;
   const size_t y_elem = p.y_f32 ? sizeof(float) : sizeof(__half);
 
-  // Activation vectors four at a time (one stream of the weights per four), then a pair, then
-  // a single one: 7 = 4 + 2 + 1.
+  // Activation vectors four at a time (one stream of the weights per four), then a pair or a
+  // single one; three left over go through the quad kernel as well, the fourth table set
+  // repeating the third vector and its results being dropped (cheaper than a pair plus one).
   GemvParams pq = p, pp = p;
   GemvKernel quad_kern = nullptr, pair_kern = nullptr;
-  if (batch >= 4) {
+  if (batch >= 3) {
     pq.NT = 4 * p.NT;   // quarter ids; those a ragged last tile does not have are skipped by the kernel
     plan_grid(cus, 4, &pq);
     quad_kern = pick_quad_kernel(q, z != nullptr, shared, gg);
     if (!quad_kern) return LUTGEMM_EUNSUPPORTED;
   }
-  if (batch % 4 >= 2) {
+  if (batch % 4 == 2) {
     const int last_chunks = p.nchunks - 128 * (p.NT - 1);
     pp.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);   // half tiles
     plan_grid(cus, 2, &pp);
@@ -1295,13 +1297,16 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     if (!pair_kern) return LUTGEMM_EUNSUPPORTED;
   }
   for (int b = 0; b < batch;) {
-    const int take = batch - b >= 4 ? 4 : (batch - b >= 2 ? 2 : 1);
+    const int left = batch - b;
+    const int take = left >= 3 ? 4 : left;          // kernel width: 4, 2 or 1
+    const int live = left >= 4 ? 4 : left;          // vectors it really computes
     GemvParams pb = take == 4 ? pq : (take == 2 ? pp : p);
     GemvKernel kb = take == 4 ? quad_kern : (take == 2 ? pair_kern : kern);
     pb.x = static_cast<const __half*>(x) + (int64_t)b * n;
     pb.partial = partials + (int64_t)b * m_pad;
     pb.counters = counters + (int64_t)b * 256;
     pb.y = static_cast<char*>(y) + (int64_t)b * m * y_elem;
+    pb.batch = live;
     const int row_units = take == 4 ? (pb.RB + 1) / 2 : pb.RB;
     pb.range_base = row_units / pb.row_splits;
     pb.range_rem = row_units % pb.row_splits;
@@ -1309,7 +1314,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     if (hipLaunchKernel(reinterpret_cast<const void*>(kb), dim3(pb.KG, pb.row_splits), dim3(kThreads), args, 0,
                         stream) != hipSuccess)
       return LUTGEMM_EHIP;
-    b += take;
+    b += live;
   }
   return LUTGEMM_OK;
 }

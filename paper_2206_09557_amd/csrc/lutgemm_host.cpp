@@ -300,9 +300,10 @@ size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int b
   // partial per (K group, activation vector, row of an even number of row blocks); four
   // vectors at a time split K over quarter tiles, two over half tiles, so up to four (two)
   // times as many groups as tiles can occur
-  const size_t groups = (size_t)s.NT * (batch >= 4 ? 4 : (batch >= 2 ? 2 : 1));
+  const size_t groups = (size_t)s.NT * (batch >= 3 ? 4 : (batch >= 2 ? 2 : 1));
   const size_t rows = (size_t)(s.RB + (s.RB & 1)) * kRowsPerBlock;
-  return (size_t)32768 + (size_t)524288 + groups * batch * rows * sizeof(float);
+  const size_t vectors = (size_t)batch + (batch % 4 == 3 ? 1 : 0);   // three left over run as four
+  return (size_t)32768 + (size_t)524288 + groups * vectors * rows * sizeof(float);
 }
 
 int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int mu, int mode,

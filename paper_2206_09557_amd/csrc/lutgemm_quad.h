@@ -121,7 +121,8 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
 #pragma unroll
   for (int b = 0; b < kBuildPasses; ++b) {
     const int v = 2 * ((wave + b * kWaves) >> 3) + half;
-    xraw[b] = *reinterpret_cast<const u32x4*>(xp + (int64_t)v * p.n);
+    // (a quad launched for three vectors builds the fourth table set from the third vector)
+    xraw[b] = *reinterpret_cast<const u32x4*>(xp + (int64_t)min(v, p.batch - 1) * p.n);
   }
 
   // planes fetched together: all up to four; beyond that half of them, or two where every
