@@ -399,9 +399,26 @@ __device__ __forceinline__ void lane_tables(int lane, uint32_t (&lane_base)[4], 
 // AMODE: how the lanes get their scales (see above).
 // first_tile: the partials are written; otherwise they are added to those of the earlier
 // tiles of the K group (each (wave, row block) pair is always served by the same wave).
+// A row's result leaves a wavefront either as a partial sum for the cross-group reduction
+// or, when the launch has a single K group of a single tile (n <= 1024), directly as y:
+// nothing is left to add, and the trip through the workspace and the arrival counter
+// would be most of the run time of so small a product.
+__device__ __forceinline__ void store_row_sum(const GemvParams& p, float* partial, bool direct, int row, float v) {
+  if (direct) {
+    if (row < p.m) {
+      if (p.y_f32)
+        static_cast<float*>(p.y)[row] = v;
+      else   // fp16 output, nearest even (paper table 1)
+        static_cast<__half*>(p.y)[row] = __float2half_rn(v);
+    }
+  } else {
+    store_device_coherent(partial + row, v);
+  }
+}
+
 template <int Q, int T, int AMODE, bool HAS_Z, int kDepth>
 __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int kt, int rb0, int rb1, float* partial,
-                                          bool first_tile) {
+                                          bool first_tile, bool direct) {
   using U = Unit<Q, 0, Q, T, AMODE, HAS_Z>;
   int lane = threadIdx.x & 63;
   // Everything derived from the lane id below belongs to this tile only: the empty asm
@@ -438,7 +455,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
                                               acc, &prev);
       int row_in_block;
       const float s = quad_rows_reduce(acc, lane, &row_in_block) + prev;
-      store_device_coherent(partial + rb * 16 + row_in_block, s);
+      store_row_sum(p, partial, direct, rb * 16 + row_in_block, s);
     }
   } else {
   // Units of the workgroup: u = 0 .. n_units-1 (row block rb0 + u).  A wavefront starts with
@@ -497,7 +514,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
       if (cur >= n_units) break;
       if (kEarly) load_unit(u[0], p, tile_base, rb0 + cur, lane, grp, partial, out_row, !first_tile);   // no fetch in flight at the exit above
     }
-    if (lane_row < n_parked) store_device_coherent(partial + parked_rb * 16 + out_row, parked);
+    if (lane_row < n_parked) store_row_sum(p, partial, direct, parked_rb * 16 + out_row, parked);
   }
   }   // Q <= 4
 }
@@ -590,18 +607,19 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
   int rb0, rb1;
   row_range(p, &rb0, &rb1);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
+  const bool direct = p.NT == 1;   // one tile, hence one K group: the sums of the tile are y
 
   for (int ti = 0; ti < p.TPG; ++ti) {
     const int kt = kg * p.TPG + ti;
     if (kt >= p.NT) break;
     if (ti > 0) __syncthreads();   // every lookup of the previous tile is done before its tables are overwritten
     if (min(128, p.nchunks - 128 * kt) > 64)
-      tile_body<Q, 2, AM2, HAS_Z, prefetch_depth(Q, AM2)>(p, lut, kt, rb0, rb1, partial, ti == 0);
+      tile_body<Q, 2, AM2, HAS_Z, prefetch_depth(Q, AM2)>(p, lut, kt, rb0, rb1, partial, ti == 0, direct);
     else
-      tile_body<Q, 1, AM1, HAS_Z, prefetch_depth(Q, AM1)>(p, lut, kt, rb0, rb1, partial, ti == 0);
+      tile_body<Q, 1, AM1, HAS_Z, prefetch_depth(Q, AM1)>(p, lut, kt, rb0, rb1, partial, ti == 0, direct);
   }
 
-  finish_row_range<1>(p, lut, rs, rb0, rb1);
+  if (!direct) finish_row_range<1>(p, lut, rs, rb0, rb1);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -45,6 +45,7 @@ CASES = [
     (130, 1032, 5, 24, "greedy_z"),      # g % 16 != 0, second tile holds one chunk
     (96, 1048, 3, 8, "rtn"),             # ragged tile AND split groups
     (200, 1024, 3, 128, "alt"),          # alternating BCQ scales (not ordered by plane)
+    (130, 1000, 6, 40, "greedy_z"),      # single ragged tile (y written without the cross-group pass), q > 4
 ]
 
 
@@ -77,10 +78,11 @@ def test_every_q(q):
         check_parity(run(p, x, f32_out=True), _oracle_full(p, x), x, _bound(p), f32_out=True)
 
 
+@pytest.mark.parametrize("n", [2048, 1024])   # 1024: a single tile, the left-over vector's y is written directly
 @pytest.mark.parametrize("batch", [1, 2, 5, 32])
-def test_gemm_batches(batch):
-    print(f"case batch={batch}", flush=True)
-    m, n, q, g = 333, 2048, 3, 128
+def test_gemm_batches(batch, n):
+    print(f"case batch={batch} n={n}", flush=True)
+    m, q, g = 333, 3, 128
     W = synth.weights_fp16(m, n, seed=3000)
     X = synth.activations_fp16(n, seed=3500 + batch, batch=batch)
     for mode in ("greedy", "greedy_z"):
