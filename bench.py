@@ -156,14 +156,45 @@ def main():
         b.record(stream)
         torch.cuda.synchronize()
         mean_us[li] = a.elapsed_time(b) * 1e3 / reps
-    med_us = mean_us
+    # the same shape with ONE weight copy: whatever the last-level cache keeps of it stays
+    # there between launches ("hot"; not a figure a decoder sees, where every layer has
+    # weights of its own)
+    hot_us = np.zeros(nL)
+    for li, ent in enumerate(layers):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for s in range(3):
+            launch(ent, 0)
+        a.record(stream)
+        for s in range(reps):
+            launch(ent, 0)
+        b.record(stream)
+        torch.cuda.synchronize()
+        hot_us[li] = a.elapsed_time(b) * 1e3 / reps
+
+    # ---- yardstick: what a kernel that only reads gets out of this device's memory, in the
+    # access shape of the weight stream, over 1 GiB (far beyond the last-level cache)
+    probe_bytes = 1 << 30
+    probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device="cuda").random_(0, 256)
+    probe_sink = torch.empty(8192, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        L.lutgemm_stream_read(probe_src, probe_bytes, probe_sink, 32768, sptr)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(10):
+        L.lutgemm_stream_read(probe_src, probe_bytes, probe_sink, 32768, sptr)
+    b.record(stream)
+    torch.cuda.synchronize()
+    stream_read_gbs = probe_bytes / (a.elapsed_time(b) * 1e-3 / 10) / 1e9
+    del probe_src
 
     per_layer = []
     for li, ent in enumerate(layers):
         gbs = ent["bytes"] / (mean_us[li] * 1e-6) / 1e9
         per_layer.append({"layer": ent["name"], "m": ent["m"], "n": ent["n"], "bytes": ent["bytes"],
                           "us_alone_back_to_back": round(float(mean_us[li]), 2),
-                          "gbs": round(gbs, 1), "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4)})
+                          "gbs": round(gbs, 1), "frac_of_8TBs": round(gbs / HBM_PEAK_GBS, 4),
+                          "frac_of_stream_read": round(gbs / stream_read_gbs, 4),
+                          "us_same_weight_copy": round(float(hot_us[li]), 2)})
 
     # ---- small batch on the FC1 shape (section 6 of the paper), outside the timed region:
     # the lookup path (lutgemm_gemm) and the matrix-core path (lutgemm_gemm_mfma) side by side ----
@@ -218,6 +249,9 @@ def main():
                                "greedy BCQ q=3 g=128, x fp16, batch 1, fp32 accumulate, fp16 out",
                    "gemvs_per_step": nL, "weight_copies_rotated": args.copies},
         "effective_gbs": round(step_gbs, 1), "frac_of_hbm_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+        "stream_read_probe": {"gbs": round(stream_read_gbs, 1), "bytes": probe_bytes,
+                              "kernel": "lutgemm_stream_read_kernel (read-only, 16 B per lane)"},
+        "frac_of_stream_read": round(step_gbs / stream_read_gbs, 4),
         "per_layer": per_layer,
         "fc1_batch_sweep": batch_sweep,
         "paper_context": {"fc1_ms": PAPER_A100_FC1_MS, "hardware": "A100-80GB (paper table 1)"},
@@ -251,9 +285,21 @@ def cpu_baseline(ent):
     nrows = int(min(m, max(256, 256 * 10.0 / max(t_probe, 1e-4))))
     t, used = timed(nrows)
     us_full = t * (m / nrows) * 1e6
+    # the smallest workload (one 1024 x 1024 GEMV) on a single thread, whole
+    from paper_2206_09557_amd import synth
+    import paper_2206_09557_amd as L
+    Ws = synth.weights_fp16(1024, 1024, seed=1000)
+    bs, als, _ = L.lutgemm_pack_bcq(Ws, Q, G)
+    xs = synth.activations_fp16(1024, seed=1500)
+    c_oracle.gemv_packed(bs, als, None, xs, 1024, 1024, Q, G, nthreads=1)
+    t0 = time.perf_counter()
+    for _ in range(5):
+        c_oracle.gemv_packed(bs, als, None, xs, 1024, 1024, Q, G, nthreads=1)
+    small_us = (time.perf_counter() - t0) / 5 * 1e6
     return {"value": round(us_full, 1), "unit": "us/GEMV", "cores": int(used), "kind": "oracle",
             "sample": f"fp64 C oracle on {nrows} of {m} rows of the FC1 49152x12288 GEMV "
-                      f"({t:.2f} s measured), scaled by m/rows"}
+                      f"({t:.2f} s measured), scaled by m/rows",
+            "gemv_1024x1024_one_thread_us": round(small_us, 1)}
 
 
 if __name__ == "__main__":

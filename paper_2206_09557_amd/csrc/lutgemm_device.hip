@@ -1229,6 +1229,34 @@ void plan_planes_grid(int cus, int waves, int batch, GemvParams* p) {
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------
+// Measurement aid: a kernel that only reads.  It walks a buffer front to back the way the
+// GEMV kernel walks the packed weights (16 bytes per lane, consecutive lanes on consecutive
+// addresses, several fetches in flight per lane) and keeps an XOR of everything it saw, so
+// that its rate is what this device delivers to a pure stream of that shape: the yardstick
+// next to the nominal HBM figure.
+constexpr int kProbeGroups = 512;    // two 1024-thread workgroups per compute unit
+constexpr int kProbeThreads = 1024;
+constexpr int kProbeUnroll = 8;      // independent 16-byte fetches per lane
+
+__global__ __launch_bounds__(kProbeThreads) void lutgemm_stream_read_kernel(const u32x4* src, int64_t n16, uint32_t* sink) {
+  const int64_t stride = (int64_t)gridDim.x * kProbeThreads;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x;
+  for (; i + (kProbeUnroll - 1) * stride < n16; i += kProbeUnroll * stride) {
+    u32x4 v[kProbeUnroll];
+#pragma unroll
+    for (int j = 0; j < kProbeUnroll; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+#pragma unroll
+    for (int j = 0; j < kProbeUnroll; ++j) acc ^= v[j];
+  }
+  for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  uint32_t w = acc.x ^ acc.y ^ acc.z ^ acc.w;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) w ^= (uint32_t)__shfl_xor((int)w, d, 64);
+  if ((threadIdx.x & 63) == 0) sink[blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6)] = w;
+}
+
 extern "C" {
 
 int lutgemm_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -1401,6 +1429,20 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   void* args[] = {&p};
   if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.KG, p.row_splits), dim3(waves * 64), args, 0,
                       static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return LUTGEMM_EHIP;
+  return LUTGEMM_OK;
+}
+
+int lutgemm_stream_read(const void* src, size_t bytes, void* sink, size_t sink_bytes, void* hip_stream) {
+  if (!src || !sink || bytes == 0 || bytes % 16 != 0) return LUTGEMM_EINVAL;
+  if (((uintptr_t)src & 15) != 0 || ((uintptr_t)sink & 3) != 0) return LUTGEMM_EINVAL;
+  if (sink_bytes < (size_t)kProbeGroups * (kProbeThreads / 64) * 4) return LUTGEMM_EWORKSPACE;
+  const u32x4* s = static_cast<const u32x4*>(src);
+  int64_t n16 = (int64_t)(bytes / 16);
+  uint32_t* out = static_cast<uint32_t*>(sink);
+  void* args[] = {&s, &n16, &out};
+  if (hipLaunchKernel(reinterpret_cast<const void*>(lutgemm_stream_read_kernel), dim3(kProbeGroups), dim3(kProbeThreads),
+                      args, 0, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return LUTGEMM_EHIP;
   return LUTGEMM_OK;
 }

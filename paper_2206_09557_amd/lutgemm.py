@@ -40,6 +40,7 @@ _SIGNATURES = {
     "lutgemm_gemm_mfma": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                      _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_int, _c.c_uint,
                                      _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "lutgemm_stream_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "lutgemm_strerror": (_c.c_char_p, [_c.c_int]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -191,6 +192,10 @@ def lutgemm_gemv(x, bits, alpha, z, y, q, g, mu, m, n, flags, workspace, workspa
 def lutgemm_gemm(x, bits, alpha, z, y, q, g, mu, m, n, batch, flags, workspace, workspace_bytes, stream=0):
     _check(lib().lutgemm_gemm(_addr(x), _addr(bits), _addr(alpha), _addr(z), _addr(y), q, g, mu, m, n, batch,
                               flags, _addr(workspace), workspace_bytes, stream or None), "lutgemm_gemm")
+
+
+def lutgemm_stream_read(src, nbytes, sink, sink_bytes, stream=0):
+    _check(lib().lutgemm_stream_read(_addr(src), nbytes, _addr(sink), sink_bytes, stream or None), "lutgemm_stream_read")
 
 
 def lutgemm_gemm_mfma(x, bits, alpha, z, y, q, g, mu, m, n, batch, flags, workspace, workspace_bytes, stream=0):
