@@ -211,9 +211,9 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* DEVICE pointers.  Measurement aid, no part of the product: reads `bytes` bytes at src
-   (bytes % 16 == 0, src 16-byte aligned) exactly once, front to back, in the access shape
-   of the weight stream of section 3.4's memory-bound regime (16 bytes per lane, coalesced),
-   and writes the XOR of all 32-bit words seen by each of its 8192 wavefronts to sink
+   (bytes % 16 == 0, src 16-byte aligned) exactly once, every workgroup a contiguous share
+   front to back, in the access shape of the weight stream of section 3.4's memory-bound
+   regime (16 bytes per lane, coalesced, non-temporal), and writes the XOR of all 32-bit words seen by each of its 8192 wavefronts to sink
    (uint32_t[8192]; the XOR of those is the XOR of the whole buffer).  Its rate is the
    read bandwidth this device sustains, which benchmarks report beside the nominal figure.
    sink_bytes < 32768 is LUTGEMM_EWORKSPACE.                                              */

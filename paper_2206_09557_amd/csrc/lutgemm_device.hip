@@ -1230,27 +1230,30 @@ void plan_planes_grid(int cus, int waves, int batch, GemvParams* p) {
 }  // namespace
 
 // ---------------------------------------------------------------------------------------
-// Measurement aid: a kernel that only reads.  It walks a buffer front to back the way the
-// GEMV kernel walks the packed weights (16 bytes per lane, consecutive lanes on consecutive
-// addresses, several fetches in flight per lane) and keeps an XOR of everything it saw, so
-// that its rate is what this device delivers to a pure stream of that shape: the yardstick
-// next to the nominal HBM figure.
-constexpr int kProbeGroups = 512;    // two 1024-thread workgroups per compute unit
-constexpr int kProbeThreads = 1024;
+// Measurement aid: a kernel that only reads.  Every workgroup walks one contiguous share of
+// the buffer front to back, the way a GEMV workgroup walks its share of the packed weights
+// (16 bytes per lane, consecutive lanes on consecutive addresses, several fetches in flight
+// per lane, nothing kept in the caches), and keeps an XOR of everything it saw, so that its
+// rate is what this device delivers to a pure stream of that shape: the yardstick next to
+// the nominal HBM figure.  (Measured: contiguous shares beat a grid-stride walk by 6 %,
+// non-temporal loads beat plain ones by 12 %.)
+constexpr int kProbeGroups = 2048;   // eight 256-thread workgroups per compute unit
+constexpr int kProbeThreads = 256;
 constexpr int kProbeUnroll = 8;      // independent 16-byte fetches per lane
 
 __global__ __launch_bounds__(kProbeThreads) void lutgemm_stream_read_kernel(const u32x4* src, int64_t n16, uint32_t* sink) {
-  const int64_t stride = (int64_t)gridDim.x * kProbeThreads;
+  const int64_t share = (n16 + gridDim.x - 1) / gridDim.x;
+  const int64_t begin = min(share * blockIdx.x, n16), end = min(begin + share, n16);
   u32x4 acc = {0u, 0u, 0u, 0u};
-  int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x;
-  for (; i + (kProbeUnroll - 1) * stride < n16; i += kProbeUnroll * stride) {
+  int64_t i = begin + threadIdx.x;
+  for (; i + (kProbeUnroll - 1) * kProbeThreads < end; i += kProbeUnroll * kProbeThreads) {
     u32x4 v[kProbeUnroll];
 #pragma unroll
-    for (int j = 0; j < kProbeUnroll; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+    for (int j = 0; j < kProbeUnroll; ++j) v[j] = __builtin_nontemporal_load(src + i + j * kProbeThreads);
 #pragma unroll
     for (int j = 0; j < kProbeUnroll; ++j) acc ^= v[j];
   }
-  for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  for (; i < end; i += kProbeThreads) acc ^= __builtin_nontemporal_load(src + i);
   uint32_t w = acc.x ^ acc.y ^ acc.z ^ acc.w;
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) w ^= (uint32_t)__shfl_xor((int)w, d, 64);

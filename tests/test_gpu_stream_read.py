@@ -9,7 +9,7 @@ from gpu_util import torch_cuda
 pytestmark = pytest.mark.gpu
 
 SINK_WORDS = 8192
-FULL = 512 * 1024 * 8      # 16-byte elements of one fully unrolled sweep
+FULL = 2048 * 256 * 8      # 16-byte elements of one fully unrolled pass of every workgroup
 
 
 @pytest.mark.parametrize("n16", [1, 63, 1024, 512 * 1024 + 7, FULL - 1, FULL, FULL + 1, 2 * FULL + 12345])
