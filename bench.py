@@ -235,8 +235,22 @@ def main():
         e.record(stream)
         torch.cuda.synchronize()
         us_mfma = a.elapsed_time(e) * 1e3 / 20
+        def gemm_auto(step):   # lutgemm_gemm left to choose between the two
+            c = step % args.copies
+            L.lutgemm_gemm(xb, fc1["bits"][c], fc1["alpha"][c], None, yb, Q, G, MU, fc1["m"], fc1["n"], b,
+                           L.LUTGEMM_Y_F16 | L.LUTGEMM_PATH_AUTO, wsg, wsb, sptr)
+
+        for s in range(3):
+            gemm_auto(s)
+        a.record(stream)
+        for s in range(20):
+            gemm_auto(s)
+        e.record(stream)
+        torch.cuda.synchronize()
+        us_auto = a.elapsed_time(e) * 1e3 / 20
         batch_sweep.append({"batch": b, "lut_us": round(us, 2), "lut_us_per_vector": round(us / b, 2),
-                            "mfma_us": round(us_mfma, 2), "mfma_us_per_vector": round(us_mfma / b, 2)})
+                            "mfma_us": round(us_mfma, 2), "mfma_us_per_vector": round(us_mfma / b, 2),
+                            "auto_us": round(us_auto, 2)})
         del xb, yb, wsg
 
     out = {

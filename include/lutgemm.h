@@ -113,7 +113,14 @@ enum {
      has the scale 2^i * alpha_0, as appendix C gives for uniformly quantised weights
      (buffer of lutgemm_alpha_shared_bytes, written by lutgemm_share_scales).  Requires z.
      Results are bit-for-bit those of the per-plane layout holding the same scales.       */
-  LUTGEMM_ALPHA_SHARED = 2
+  LUTGEMM_ALPHA_SHARED = 2,
+  /* lutgemm_gemm only: let the library take the matrix-core path (lutgemm_gemm_mfma) where
+     it measured faster on MI355X and is applicable (group size a multiple of 64, per-plane
+     scales): from five activation vectors on, and from four on layers of at most 2^27
+     weights.  Section 6 of the paper: the lookup path pays per vector, the matrix cores
+     do not.  Either path meets the same tolerance; which one ran is decided by shape and
+     batch only, so results stay reproducible.                                            */
+  LUTGEMM_PATH_AUTO = 4
 };
 
 /* Buffer sizes in bytes of the packed layouts above (section 3.4 eq. 4, padded to the
@@ -203,9 +210,9 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
    scale per group (section 3.2: y = sum_i A_i o (B_i . x); offset term of eq. 3).  Its
    time does not grow with batch up to 16 vectors, where the lookup path's does (the
    limitation discussed in section 6), so it is the faster of the two from a batch of
-   about eight.  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
+   four to seven, depending on the layer (LUTGEMM_PATH_AUTO).  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
    included when n % 64 == 0): LUTGEMM_EUNSUPPORTED otherwise, as is
-   LUTGEMM_ALPHA_SHARED.  Bitwise reproducible.                                          */
+   LUTGEMM_ALPHA_SHARED or LUTGEMM_PATH_AUTO.  Bitwise reproducible.                     */
 int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
                       int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                       void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "liblutgemm.so")
 
 LUTGEMM_OK, LUTGEMM_EINVAL, LUTGEMM_EUNSUPPORTED, LUTGEMM_EWORKSPACE, LUTGEMM_EHIP = 0, -1, -2, -3, -4
 LUTGEMM_Q_GREEDY, LUTGEMM_Q_GREEDY_MEAN_OFFSET, LUTGEMM_Q_UNIFORM_RTN, LUTGEMM_Q_ALTERNATING = 0, 1, 2, 3
-LUTGEMM_Y_F16, LUTGEMM_Y_F32, LUTGEMM_ALPHA_SHARED = 0, 1, 2
+LUTGEMM_Y_F16, LUTGEMM_Y_F32, LUTGEMM_ALPHA_SHARED, LUTGEMM_PATH_AUTO = 0, 1, 2, 4
 
 _c = ctypes
 _SIGNATURES = {

@@ -48,7 +48,7 @@ def make_workspace(nbytes, stream=None):
     return d_ws
 
 
-def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, shared=False):
+def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, shared=False, auto=False):
     """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x; lutgemm_gemm_mfma if mfma) for the packed layer.
     y is pre-filled with NaN: it must be fully overwritten, never read."""
     torch = torch_cuda()
@@ -67,6 +67,8 @@ def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, sha
     if shared:   # scales in the shared-scale layout
         flags |= L.LUTGEMM_ALPHA_SHARED
         d_alpha = p.d_alpha_shared
+    if auto:     # lutgemm_gemm picks the path
+        flags |= L.LUTGEMM_PATH_AUTO
     torch.cuda.synchronize()
     if mfma:
         L.lutgemm_gemm_mfma(d_x, p.d_bits, d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,

@@ -138,7 +138,7 @@ def test_argument_validation_returns_codes_without_gpu():
     assert gemv(g=12, n=96) == L.LUTGEMM_EINVAL              # g % 8
     assert gemv(q=0) == L.LUTGEMM_EINVAL and gemv(q=9) == L.LUTGEMM_EINVAL
     assert gemv(mu=4) == L.LUTGEMM_EUNSUPPORTED
-    assert gemv(flags=4) == L.LUTGEMM_EUNSUPPORTED           # unknown flag
+    assert gemv(flags=8) == L.LUTGEMM_EUNSUPPORTED           # unknown flag
     assert gemv(flags=2) == L.LUTGEMM_EINVAL                 # shared-scale layout without offsets
     assert gemv(wsb=16) == L.LUTGEMM_EWORKSPACE
     assert lib.lutgemm_gemm(p16, p16, p16, None, p16, 3, 64, 8, 16, 64, 33, 0, p16, 1 << 20, None) == L.LUTGEMM_EUNSUPPORTED

@@ -197,6 +197,27 @@ def test_mfma_path_rejects_groups_not_multiple_of_64():
 
 # ---- shared-scale layout (one scale per group, appendix C) ----
 
+def test_auto_path_is_one_of_the_two():
+    # LUTGEMM_PATH_AUTO: by shape and batch alone, the matrix-core path from five vectors on
+    # (four on small layers) where it applies, else the lookup path; bit for bit that path's y
+    m, n, q = 300, 2048, 3
+    W = synth.weights_fp16(m, n, seed=5600)
+    for g, batch, want_mfma in [(128, 8, True), (128, 5, True), (128, 4, True), (128, 3, False), (128, 1, False),
+                                (32, 8, False), (0, 6, True)]:
+        print(f"case g={g} batch={batch}", flush=True)
+        p = Packed.from_weights(W, q, g, MODES["greedy_z"])
+        X = synth.activations_fp16(n, seed=5601 + batch, batch=batch)
+        y_auto = run(p, X, f32_out=True, auto=True)
+        y_want = run(p, X, f32_out=True, mfma=want_mfma)
+        np.testing.assert_array_equal(y_auto, y_want)
+        for b in range(batch):
+            check_parity(y_auto[b], _oracle_full(p, X[b]), X[b], _bound(p), f32_out=True)
+    # shared scales: always the lookup path
+    p = Packed.from_weights(W, q, 128, MODES["rtn"]).share()
+    X = synth.activations_fp16(n, seed=5610, batch=8)
+    np.testing.assert_array_equal(run(p, X, f32_out=True, auto=True, shared=True), run(p, X, f32_out=True, shared=True))
+
+
 SHARED_CASES = [
     (300, 2048, 3, 32, None),     # small groups: the scale bytes matter most here
     (300, 2048, 2, 64, None),
