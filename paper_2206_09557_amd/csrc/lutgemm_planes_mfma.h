@@ -168,13 +168,16 @@ __device__ __forceinline__ void planes_compute(const GemvParams& p, const Planes
 #pragma unroll
     for (int i = 0; i < Q; ++i) acc[i][nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
   }
-  constexpr int cols_per_blk = 32 * T;
   const uint32_t* my_stage = stage + sub * 4 + (col >> 2);
   const u32x2* my_sign = sign + (lane & 31);
   const f16x8* my_x = Xs + (T * sub) * NB16 + col;
   const unsigned char* my_alpha = astage + sub * Q * 8;
   const unsigned char* my_z = zstage + sub * 8;
   int seg = 0;                      // group segment of the current block, relative to t.G0
+  // group ends are counted in blocks (no division in the loop): g is a multiple of the 64
+  // columns of a block pair, and so is the distance from the tile's first column to a group end
+  const int seg_blocks = p.g / (32 * T);
+  int left = (p.g - (1024 * t.kt) % p.g) / (32 * T);   // blocks until the first group ends
   u32x2 a4[Q], z4;                  // scales / offsets of segment `seg` for this lane's four rows
 #pragma unroll
   for (int i = 0; i < Q; ++i) a4[i] = *reinterpret_cast<const u32x2*>(my_alpha + i * 8);
@@ -217,8 +220,8 @@ __device__ __forceinline__ void planes_compute(const GemvParams& p, const Planes
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) sx[nb] += blksum[j * 32 + nb * 16 + col];
         }
-        const int next_seg = (1024 * t.kt + (j + 1) * cols_per_blk) / p.g - t.G0;
-        if (j == t.nblk - 1 || next_seg != seg) {   // wave-uniform: the group ends here (section 3.2 rule 2)
+        --left;
+        if (j == t.nblk - 1 || left == 0) {   // wave-uniform: the group ends here (section 3.2 rule 2)
 #pragma unroll
           for (int i = 0; i < Q; ++i) {
 #pragma unroll
@@ -240,7 +243,8 @@ __device__ __forceinline__ void planes_compute(const GemvParams& p, const Planes
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) sx[nb] = 0.0f;
           }
-          seg = min(next_seg, t.nseg - 1);   // the next group's scales, used when that group ends
+          left = seg_blocks;
+          seg = min(seg + 1, t.nseg - 1);   // the next group's scales, used when that group ends
 #pragma unroll
           for (int i = 0; i < Q; ++i) a4[i] = *reinterpret_cast<const u32x2*>(my_alpha + (seg * 4 * Q + i) * 8);
           if (HAS_Z) z4 = *reinterpret_cast<const u32x2*>(my_z + seg * 32);
