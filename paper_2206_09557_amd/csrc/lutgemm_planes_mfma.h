@@ -350,17 +350,37 @@ __global__ __launch_bounds__(PlanesCfg<Q>::kThreadsM) void lutgemm_planes_mfma_k
     const PlanesTile t0 = planes_tile_info(p, kt0, Q);
     planes_fetch(raw, p, t0, rb0 + wave, lane);
   }
+  // The X tile of the NEXT K tile is fetched into registers while the current tile is being
+  // multiplied, so that a tile switch costs two barriers and an LDS write, not a trip to memory.
+  constexpr int kXPerThread = 128 * NB16 / kThr;
+  static_assert(128 * NB16 % kThr == 0, "X tile elements per thread");
+  u32x4 xnext[kXPerThread];
+  auto fetch_x_tile = [&](int kt) {
+    const int chunks = min(128, p.nchunks - 128 * kt);
+#pragma unroll
+    for (int e = 0; e < kXPerThread; ++e) {
+      const int idx = threadIdx.x + e * kThr;
+      const int c = idx / NB16, n = idx % NB16;
+      // clamped address, the load itself is unconditional; empty slots are zeroed when the
+      // tile is written to LDS (no use of the value here: the fetch stays in flight)
+      xnext[e] = *reinterpret_cast<const u32x4*>(p.x + (int64_t)min(n, p.batch - 1) * p.n +
+                                                 (int64_t)(128 * kt + min(c, chunks - 1)) * 8);
+    }
+  };
+  constexpr bool kAheadX = Q * NB <= 6;   // (more planes x vectors: no registers to hold the tile)
+  if (kAheadX) fetch_x_tile(kt0);
   for (int kt = kt0; kt < kt1; ++kt) {
     const PlanesTile t = planes_tile_info(p, kt, Q);
     __syncthreads();   // the previous tile's X is no longer read (first pass: nothing to wait for)
-    for (int idx = threadIdx.x; idx < 128 * NB16; idx += kThr) {
+    if (!kAheadX) fetch_x_tile(kt);
+#pragma unroll
+    for (int e = 0; e < kXPerThread; ++e) {
+      const int idx = threadIdx.x + e * kThr;
       const int c = idx / NB16, n = idx % NB16;
-      u32x4 v = u32x4{0u, 0u, 0u, 0u};
-      if (c < t.chunks && n < p.batch)
-        v = *reinterpret_cast<const u32x4*>(p.x + (int64_t)n * p.n + (int64_t)(128 * kt + c) * 8);
-      Xs[idx] = v;
+      Xs[idx] = (c < t.chunks && n < p.batch) ? xnext[e] : u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
+    if (kAheadX) fetch_x_tile(min(kt + 1, kt1 - 1));
     if (HAS_Z) {   // sum of the activations of every block (the offset term needs it per group)
       for (int idx = threadIdx.x; idx < 16 * NB16; idx += kThr) {
         const int j = idx / NB16, n = idx % NB16;
