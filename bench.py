@@ -298,6 +298,12 @@ def cpu_baseline(ent):
     t_probe, used = timed(256)
     nrows = int(min(m, max(256, 256 * 10.0 / max(t_probe, 1e-4))))
     t, used = timed(nrows)
+    reps = 1
+    while t < 10.0 and nrows == m and reps < 64:   # the whole GEMV takes under ten seconds: repeat it
+        dt, used = timed(nrows)
+        t += dt
+        reps += 1
+    t /= reps
     us_full = t * (m / nrows) * 1e6
     # the smallest workload (one 1024 x 1024 GEMV) on a single thread, whole
     from paper_2206_09557_amd import synth
@@ -312,7 +318,7 @@ def cpu_baseline(ent):
     small_us = (time.perf_counter() - t0) / 5 * 1e6
     return {"value": round(us_full, 1), "unit": "us/GEMV", "cores": int(used), "kind": "oracle",
             "sample": f"fp64 C oracle on {nrows} of {m} rows of the FC1 49152x12288 GEMV "
-                      f"({t:.2f} s measured), scaled by m/rows",
+                      f"({t:.2f} s each, mean of {reps} runs), scaled by m/rows",
             "gemv_1024x1024_one_thread_us": round(small_us, 1)}
 
 
