@@ -165,9 +165,6 @@ __device__ __forceinline__ float quad_rows_reduce(const float (&acc)[4], int lan
 // group), alpha_0, and that plane i has the scale 2^i * alpha_0 (appendix C: the scales of
 // uniformly quantised weights): one fetch of four rows instead of four rows x q planes.
 enum { kAlphaQuad = 0, kAlphaPerSlot = 1, kAlphaPerChunk = 2, kAlphaShared = 4 };
-// Also carried in the mode: fetch a wavefront's first unit before the tables are built (GEMV
-// kernel, short row ranges: see tile_body).
-enum { kEarlyFirst = 8 };
 
 // What one wavefront fetches for planes I0 .. I0+QP-1 of one (K tile, row block) unit of a
 // Q-plane layer.  (Layers of up to four planes are fetched whole; more planes go in two
@@ -473,11 +470,13 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   if (threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = kWaves;   // units 0..kWaves-1 are taken
   U u[kDepth + 1];
   int cur = wave;                               // unit being computed (or about to be)
-  // kEarlyFirst (chosen by the host for short row ranges, one or two units per wavefront):
-  // the first unit is fetched before the tables are built, so that its latency and that of
-  // the activations overlap.  On long ranges this does not pay: every wavefront of the
-  // device then floods the memory system at once and the activations queue behind.
-  constexpr bool kEarly = kDepth == 0 && (AMODE & kEarlyFirst) != 0;
+  // kEarly (the common scale mode, which has the registers for the fetch code twice): a
+  // wavefront asks for its first unit as soon as the activations have ARRIVED and before it
+  // builds its share of the tables, so that the build overlaps the fetch.  Not before they
+  // arrive: every wavefront of the device would flood the memory system at once and the
+  // activations, which every lookup waits for, would queue behind the weights (measured).
+  constexpr bool kEarly = kDepth == 0 && AMODE == kAlphaQuad;
+  if (kEarly) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (kDepth == 1 || kEarly)
     load_unit(u[0], p, tile_base, rb0 + min(cur, u_clamp), lane, grp, partial, out_row, !first_tile);
 
@@ -953,9 +952,7 @@ GemvKernel pick_q(int q) {
 }
 
 template <bool HAS_Z, int SH>
-GemvKernel pick_mode(int q, int64_t g, bool early) {
-  if (g % 64 == 0 && early && SH == 0 && q <= 4)   // the early first fetch exists for the common case only
-    return pick_q<HAS_Z, kAlphaQuad | kEarlyFirst, kAlphaQuad | kEarlyFirst>(q);
+GemvKernel pick_mode(int q, int64_t g) {
   if (g % 64 == 0) return pick_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
   if (g % 32 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
   if (g % 16 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
@@ -963,9 +960,9 @@ GemvKernel pick_mode(int q, int64_t g, bool early) {
 }
 
 // shared: the scale buffer is in the shared-scale layout (offsets are then always present)
-GemvKernel pick_kernel(int q, bool has_z, bool shared, int64_t g, bool early) {
-  if (shared) return pick_mode<true, kAlphaShared>(q, g, early);
-  return has_z ? pick_mode<true, 0>(q, g, early) : pick_mode<false, 0>(q, g, early);
+GemvKernel pick_kernel(int q, bool has_z, bool shared, int64_t g) {
+  if (shared) return pick_mode<true, kAlphaShared>(q, g);
+  return has_z ? pick_mode<true, 0>(q, g) : pick_mode<false, 0>(q, g);
 }
 
 // Pair kernel: a lane's dword is one chunk, so the per-chunk scale mode does not occur.
@@ -1049,10 +1046,10 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // Tuning overrides for sweeps (environment variables, read once per process; 0 = unset):
 // LUTGEMM_TPG / LUTGEMM_RS, LUTGEMM_PAIR_TPG / _RS, LUTGEMM_QUAD_TPG / _RS (K tiles per group,
-// row ranges of the three lookup kernels), LUTGEMM_MFMA_TPG, LUTGEMM_EARLY_MAX.
+// row ranges of the three lookup kernels), LUTGEMM_MFMA_TPG.
 struct Tuning {
   int tpg[3], rs[3];   // by kernel: GEMV, pair, quad
-  int mfma_tpg, early_max;
+  int mfma_tpg;
 };
 const Tuning& tuning() {
   static const Tuning t = [] {
@@ -1068,7 +1065,6 @@ const Tuning& tuning() {
     r.tpg[2] = env("LUTGEMM_QUAD_TPG");
     r.rs[2] = env("LUTGEMM_QUAD_RS");
     r.mfma_tpg = env("LUTGEMM_MFMA_TPG");
-    r.early_max = env("LUTGEMM_EARLY_MAX");
     return r;
   }();
   return t;
@@ -1320,11 +1316,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
   p.kg_stride = m_pad * (batch + (batch % 4 == 3 ? 1 : 0));   // room for the dropped fourth vector of a quad of three
 
-  // short row ranges (few units per wavefront): fetch the first unit before the tables are built
-  const int early_env = tuning().early_max;   // tuning override: rounds of units per wavefront, negative = never
-  const int early_max = early_env == 0 ? 2 : (early_env < 0 ? 0 : early_env);
-  const bool early = (p.RB + p.row_splits - 1) / p.row_splits <= early_max * kWaves;
-  GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg, early);
+  GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
 
   uint32_t* counters = static_cast<uint32_t*>(workspace);
