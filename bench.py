@@ -276,14 +276,14 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers[2])
+        out["cpu_baseline"] = cpu_baseline(layers[2], layers)
     print(json.dumps(out), flush=True)
     return 0
 
 
-def cpu_baseline(ent):
+def cpu_baseline(ent, all_layers=()):
     """The fp64 C oracle, as it stands, on the host cores: a row sample of the FC1 GEMV
-    sized to about ten seconds, scaled to a whole GEMV."""
+    sized to about ten seconds, scaled to a whole GEMV; then one whole GEMV of every layer."""
     from oracle import c_oracle
     bits, alpha, x = ent["host"]
     m, n = ent["m"], ent["n"]
@@ -316,7 +316,15 @@ def cpu_baseline(ent):
     for _ in range(5):
         c_oracle.gemv_packed(bs, als, None, xs, 1024, 1024, Q, G, nthreads=1)
     small_us = (time.perf_counter() - t0) / 5 * 1e6
+    per_layer = {}
+    if t * (m / nrows) < 5.0:   # a whole GEMV takes seconds: time each layer of the step once
+        for e in all_layers:
+            b_, a_, x_ = e["host"]
+            t0 = time.perf_counter()
+            c_oracle.gemv_packed(b_, a_, None, x_, e["m"], e["n"], Q, G)
+            per_layer[e["name"]] = round((time.perf_counter() - t0) * 1e6, 1)
     return {"value": round(us_full, 1), "unit": "us/GEMV", "cores": int(used), "kind": "oracle",
+            "per_layer_us": per_layer,
             "sample": f"fp64 C oracle on {nrows} of {m} rows of the FC1 49152x12288 GEMV "
                       f"({t:.2f} s each, mean of {reps} runs), scaled by m/rows",
             "gemv_1024x1024_one_thread_us": round(small_us, 1)}
