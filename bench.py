@@ -321,7 +321,7 @@ def cpu_baseline(ent, all_layers=()):
         for e in all_layers:
             b_, a_, x_ = e["host"]
             t0 = time.perf_counter()
-            c_oracle.gemv_packed(b_, a_, None, x_, e["m"], e["n"], Q, G)
+            c_oracle.gemv_packed(b_, a_, None, x_, e["m"], e["n"], Q, G, nthreads=int(used))   # (the one-thread run above left the thread count at one)
             per_layer[e["name"]] = round((time.perf_counter() - t0) * 1e6, 1)
     return {"value": round(us_full, 1), "unit": "us/GEMV", "cores": int(used), "kind": "oracle",
             "per_layer_us": per_layer,
