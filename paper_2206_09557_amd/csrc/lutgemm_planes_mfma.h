@@ -24,7 +24,7 @@ struct PlanesCfg {
   static constexpr int kWavesM = Q > 4 ? 4 : 8;         // wavefronts per workgroup
   static constexpr int kThreadsM = kWavesM * 64;
   static constexpr int kMaxSeg = 17;                    // group segments a tile can touch (g >= 64)
-  static constexpr int kStageBytes = Q * 2048;          // per wavefront: Q planes x 2 sub-slabs, regrouped
+  static constexpr int kStageBytes = Q * 2048;          // per wavefront: Q planes x 2 sub-slabs, as fetched
   static constexpr int kAlphaBytes = kMaxSeg * Q * 32;  // per wavefront: scales of one unit
   static constexpr int kZBytes = kMaxSeg * 32;          // per wavefront: offsets of one unit
   static constexpr int kAlphaPasses = (kAlphaBytes + 1023) / 1024;
@@ -42,7 +42,7 @@ constexpr int planes_lds_bytes() {
   return kXOff + 32768 * NB + C::kWavesM * (C::kStageBytes + C::kAlphaBytes + C::kZBytes);
 }
 
-// Raw data of one unit (K tile x row block) as fetched from memory, before it is regrouped in LDS.
+// Raw data of one unit (K tile x row block) as fetched from memory.
 template <int Q, bool HAS_Z>
 struct PlanesRaw {
   u32x4 w[Q][2];
@@ -91,25 +91,20 @@ __device__ __forceinline__ void planes_fetch(PlanesRaw<Q, HAS_Z>& r, const GemvP
   }
 }
 
-// Regroup a fetched unit in this wavefront's LDS staging area.  Key words: lane 4j + k holds,
-// in dword s, rows 4k..4k+3 of slot 4j + (s + k) % 4; they are stored as [plane][sub-slab]
-// [block j][slot in block][quarter k], so that the 16 dwords a matrix-core step needs are
-// consecutive.
+// Copy a fetched unit into this wavefront's LDS staging area.  The key slabs are stored as
+// they lie in memory (slab (plane, sub-slab) at dword (plane * 2 + sub-slab) * 256, lane L's
+// four dwords at 4 * L): one 16-byte store per slab and lane, free of bank conflicts.  The
+// key of (row r, slot 4j + c) is then byte r % 4 of the dword at
+// 16 * j + 4 * (r / 4) + (c - r / 4) mod 4 of the slab: a per-lane constant plus 16 * j.
 template <int Q, bool HAS_Z>
 __device__ __forceinline__ void planes_stage(const PlanesRaw<Q, HAS_Z>& r, const PlanesTile& t, int lane,
                                              uint32_t* stage, unsigned char* astage, unsigned char* zstage) {
   using C = PlanesCfg<Q>;
-  const int j = lane >> 2, k = lane & 3;
 #pragma unroll
   for (int i = 0; i < Q; ++i)
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      if (tt < t.T) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          stage[i * 512 + (tt * 16 + j) * 16 + ((s + k) & 3) * 4 + k] = r.w[i][tt][s];
-      }
-    }
+    for (int tt = 0; tt < 2; ++tt)
+      if (tt < t.T) *reinterpret_cast<u32x4*>(stage + (i * 2 + tt) * 256 + lane * 4) = r.w[i][tt];
   const int abytes = t.nseg * Q * 32;
 #pragma unroll
   for (int kk = 0; kk < C::kAlphaPasses; ++kk) {
@@ -168,7 +163,7 @@ __device__ __forceinline__ void planes_compute(const GemvParams& p, const Planes
 #pragma unroll
     for (int i = 0; i < Q; ++i) acc[i][nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
   }
-  const uint32_t* my_stage = stage + sub * 4 + (col >> 2);
+  const uint32_t* my_stage = stage + 4 * (col >> 2) + ((sub - (col >> 2)) & 3);   // (row col, slot sub) of block 0
   const u32x2* my_sign = sign + (lane & 31);
   const f16x8* my_x = Xs + (T * sub) * NB16 + col;
   const unsigned char* my_alpha = astage + sub * Q * 8;
