@@ -518,6 +518,63 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   }   // Q <= 4
 }
 
+// Sum over the K groups and store for rows [rb0 * 16, row_end): RPP rows per thread per pass,
+// KB K groups per row per batch, i.e. RPP * KB independent loads in flight per thread, because
+// every one of them goes to memory (the partials were written through by other workgroups).
+// Addresses are clamped, not predicated, so RPP and KB are chosen to fit the row range and
+// the group count (a clamped load is a wasted load); the sum over the groups of a row always
+// runs in ascending group order.
+template <int NVEC, int RPP, int KB>
+__device__ __forceinline__ void reduce_rows(const GemvParams& p, int rb0, int row_end) {
+#pragma unroll
+  for (int vec = 0; vec < NVEC; ++vec) {
+    if (NVEC == 4 && vec >= p.batch) continue;   // a quad launched for three vectors: nothing to write for the fourth
+    const float* part = NVEC == 1 ? p.partial : p.partial + (int64_t)vec * p.vec_stride;
+    for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += RPP * kThreads) {
+      const float* src[RPP];
+      float sum[RPP];
+#pragma unroll
+      for (int j = 0; j < RPP; ++j) {
+        src[j] = part + min(r0 + j * kThreads, row_end - 1);
+        sum[j] = 0.0f;
+      }
+      for (int kb = 0; kb < p.KG; kb += KB) {
+        float v[RPP][KB];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {
+          const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
+#pragma unroll
+          for (int j = 0; j < RPP; ++j) v[j][u] = load_device_coherent(src[j] + off);
+        }
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {
+          const bool live = kb + u < p.KG;
+#pragma unroll
+          for (int j = 0; j < RPP; ++j) sum[j] += live ? v[j][u] : 0.0f;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < RPP; ++j) {
+        const int r = r0 + j * kThreads;
+        if (r < row_end) {
+          if (p.y_f32)
+            static_cast<float*>(p.y)[(int64_t)vec * p.m + r] = sum[j];
+          else   // fp16 output, nearest even (paper table 1)
+            static_cast<__half*>(p.y)[(int64_t)vec * p.m + r] = __float2half_rn(sum[j]);
+        }
+      }
+    }
+  }
+}
+
+template <int NVEC, int RPP>
+__device__ __forceinline__ void reduce_rows_by_groups(const GemvParams& p, int rb0, int row_end) {
+  if (p.KG <= 12)
+    reduce_rows<NVEC, RPP, 12>(p, rb0, row_end);
+  else
+    reduce_rows<NVEC, RPP, 16>(p, rb0, row_end);
+}
+
 // Cross-group reduction by the last workgroup to arrive for a row range, for NVEC activation
 // vectors (appendix B accumulates the per-block partial outputs with atomics; here the
 // groups are added in index order by whoever arrives last, so y is reproducible bit for bit).
@@ -533,51 +590,14 @@ __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut
   }
   __syncthreads();
   if (flag[0] == 0u) return;
-  // Several rows per thread per pass, 16 K groups per row per batch: many independent loads
-  // in flight per thread, because every one of them goes to memory (the partials were
-  // written through by other workgroups).  Addresses are clamped, not predicated; the sum
-  // over the groups of a row always runs in ascending group order.
-  constexpr int kRowsPerPass = (kWaves > 8) ? 3 : 8;   // bounded by the registers of a wavefront
   const int row_end = min(rb1 * 16, p.m);
-#pragma unroll
-  for (int vec = 0; vec < NVEC; ++vec) {
-    if (NVEC == 4 && vec >= p.batch) continue;   // a quad launched for three vectors: nothing to write for the fourth
-    const float* part = NVEC == 1 ? p.partial : p.partial + (int64_t)vec * p.vec_stride;
-    for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRowsPerPass * kThreads) {
-      const float* src[kRowsPerPass];
-      float sum[kRowsPerPass];
-#pragma unroll
-      for (int j = 0; j < kRowsPerPass; ++j) {
-        src[j] = part + min(r0 + j * kThreads, row_end - 1);
-        sum[j] = 0.0f;
-      }
-      for (int kb = 0; kb < p.KG; kb += 16) {
-        float v[kRowsPerPass][16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
-#pragma unroll
-          for (int j = 0; j < kRowsPerPass; ++j) v[j][u] = load_device_coherent(src[j] + off);
-        }
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          const bool live = kb + u < p.KG;
-#pragma unroll
-          for (int j = 0; j < kRowsPerPass; ++j) sum[j] += live ? v[j][u] : 0.0f;
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < kRowsPerPass; ++j) {
-        const int r = r0 + j * kThreads;
-        if (r < row_end) {
-          if (p.y_f32)
-            static_cast<float*>(p.y)[(int64_t)vec * p.m + r] = sum[j];
-          else   // fp16 output, nearest even (paper table 1)
-            static_cast<__half*>(p.y)[(int64_t)vec * p.m + r] = __float2half_rn(sum[j]);
-        }
-      }
-    }
-  }
+  const int rows = row_end - rb0 * 16;
+  if (rows <= kThreads)
+    reduce_rows_by_groups<NVEC, 1>(p, rb0, row_end);
+  else if (rows <= 2 * kThreads)
+    reduce_rows_by_groups<NVEC, 2>(p, rb0, row_end);
+  else
+    reduce_rows_by_groups<NVEC, 3>(p, rb0, row_end);
   if (threadIdx.x == 0)            // leave the counter at zero for the next call on this workspace
     __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
