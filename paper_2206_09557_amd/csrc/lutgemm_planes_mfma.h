@@ -249,8 +249,55 @@ __device__ __forceinline__ void planes_compute(const GemvParams& p, const Planes
   }
 }
 
-// Sum of the K groups by the last workgroup to arrive for a row range, all activation vectors
-// (the GEMV kernel's final reduction with a run-time vector count and workgroup size).
+// Sum over the K groups and store for all (activation vector, row) pairs of a row range,
+// spread evenly over the threads: E pairs per thread per pass, KB groups per pair per batch
+// (E * KB independent loads in flight per thread; addresses clamped, not predicated, so KB
+// follows the group count).  The sum over the groups always runs in ascending group order.
+template <int THREADS, int E, int KB>
+__device__ __forceinline__ void reduce_rows_batch(const GemvParams& p, int rb0, int row_end) {
+  const int rows = row_end - rb0 * 16;
+  const int total = rows * p.batch;
+  for (int e0 = threadIdx.x; e0 < total; e0 += E * THREADS) {
+    const float* src[E];
+    int64_t dst[E];
+    float sum[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const int e = min(e0 + j * THREADS, total - 1);
+      const int vec = e / rows, r = rb0 * 16 + e % rows;
+      src[j] = p.partial + (int64_t)vec * p.vec_stride + r;
+      dst[j] = (int64_t)vec * p.m + r;
+      sum[j] = 0.0f;
+    }
+    for (int kb = 0; kb < p.KG; kb += KB) {
+      float v[E][KB];
+#pragma unroll
+      for (int u = 0; u < KB; ++u) {
+        const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
+#pragma unroll
+        for (int j = 0; j < E; ++j) v[j][u] = load_device_coherent(src[j] + off);
+      }
+#pragma unroll
+      for (int u = 0; u < KB; ++u) {
+        const bool live = kb + u < p.KG;
+#pragma unroll
+        for (int j = 0; j < E; ++j) sum[j] += live ? v[j][u] : 0.0f;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      if (e0 + j * THREADS < total) {
+        if (p.y_f32)
+          static_cast<float*>(p.y)[dst[j]] = sum[j];
+        else   // fp16 output, nearest even (paper table 1)
+          static_cast<__half*>(p.y)[dst[j]] = __float2half_rn(sum[j]);
+      }
+    }
+  }
+}
+
+// Cross-group reduction by the last workgroup to arrive for a row range (as in the GEMV
+// kernel, with a run-time vector count and workgroup size).
 template <int THREADS>
 __device__ __forceinline__ void finish_rows_batch(const GemvParams& p, uint32_t* flag, int rs, int rb0, int rb1) {
   __syncthreads();
@@ -260,41 +307,13 @@ __device__ __forceinline__ void finish_rows_batch(const GemvParams& p, uint32_t*
   }
   __syncthreads();
   if (flag[0] == 0u) return;
-  constexpr int kRows = 4;
   const int row_end = min(rb1 * 16, p.m);
-  for (int vec = 0; vec < p.batch; ++vec) {
-    const float* part = p.partial + (int64_t)vec * p.vec_stride;
-    for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += kRows * THREADS) {
-      float sum[kRows];
-#pragma unroll
-      for (int j = 0; j < kRows; ++j) sum[j] = 0.0f;
-      for (int kb = 0; kb < p.KG; kb += 8) {
-        float v[kRows][8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
-#pragma unroll
-          for (int j = 0; j < kRows; ++j) v[j][u] = load_device_coherent(part + min(r0 + j * THREADS, row_end - 1) + off);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const bool live = kb + u < p.KG;
-#pragma unroll
-          for (int j = 0; j < kRows; ++j) sum[j] += live ? v[j][u] : 0.0f;
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < kRows; ++j) {
-        const int r = r0 + j * THREADS;
-        if (r < row_end) {
-          if (p.y_f32)
-            static_cast<float*>(p.y)[(int64_t)vec * p.m + r] = sum[j];
-          else
-            static_cast<__half*>(p.y)[(int64_t)vec * p.m + r] = __float2half_rn(sum[j]);
-        }
-      }
-    }
-  }
+  if (p.KG <= 2)
+    reduce_rows_batch<THREADS, 8, 2>(p, rb0, row_end);
+  else if (p.KG <= 4)
+    reduce_rows_batch<THREADS, 4, 4>(p, rb0, row_end);
+  else
+    reduce_rows_batch<THREADS, 2, 8>(p, rb0, row_end);
   if (threadIdx.x == 0) __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
