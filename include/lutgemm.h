@@ -116,7 +116,7 @@ enum {
   LUTGEMM_ALPHA_SHARED = 2,
   /* lutgemm_gemm only: let the library take the matrix-core path (lutgemm_gemm_mfma) where
      it measured faster on MI355X and is applicable (group size a multiple of 64, per-plane
-     scales): from five activation vectors on, and from four on layers of at most 2^27
+     scales): from five activation vectors on, and from three on layers of at most 2^27
      weights.  Section 6 of the paper: the lookup path pays per vector, the matrix cores
      do not.  Either path meets the same tolerance; which one ran is decided by shape and
      batch only, so results stay reproducible.                                            */
@@ -210,7 +210,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
    scale per group (section 3.2: y = sum_i A_i o (B_i . x); offset term of eq. 3).  Its
    time does not grow with batch up to 16 vectors, where the lookup path's does (the
    limitation discussed in section 6), so it is the faster of the two from a batch of
-   four to seven, depending on the layer (LUTGEMM_PATH_AUTO).  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
+   three to six, depending on the layer (LUTGEMM_PATH_AUTO).  Requires a group size that is a multiple of 64 columns (g == 0, row-wise,
    included when n % 64 == 0): LUTGEMM_EUNSUPPORTED otherwise, as is
    LUTGEMM_ALPHA_SHARED or LUTGEMM_PATH_AUTO.  Bitwise reproducible.                     */
 int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,

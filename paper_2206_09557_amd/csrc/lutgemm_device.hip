@@ -1303,11 +1303,11 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   if (m > (int64_t)1 << 30 || n > (int64_t)1 << 30) return LUTGEMM_EUNSUPPORTED;
   const bool shared = (flags & LUTGEMM_ALPHA_SHARED) != 0;
   if (shared && !z) return LUTGEMM_EINVAL;   // the shared-scale form always comes with offsets
-  // Measured on MI355X (q = 2..4, seven layer shapes from 4096^2 to 49152 x 12288): the
+  // Measured on MI355X (q = 2..4, twelve layer shapes from 4096^2 to 49152 x 12288): the
   // lookup path costs about a GEMV per four vectors, the matrix-core path the same for any
-  // batch up to 16; they cross between four and six vectors, earlier on small layers.
+  // batch up to 16; they cross between three and six vectors, earlier on small layers.
   if ((flags & LUTGEMM_PATH_AUTO) != 0 && !shared && gg % 64 == 0 &&
-      (batch >= 5 || (batch == 4 && m * n <= (int64_t)1 << 27)))
+      (batch >= 5 || (batch >= 3 && m * n <= (int64_t)1 << 27)))
     return lutgemm_gemm_mfma(x, bits, alpha, z, y, q, g, mu, m, n, batch, flags & LUTGEMM_Y_F32, workspace,
                              workspace_bytes, hip_stream);
   const size_t need = lutgemm_workspace_bytes(m, n, q, g, mu, batch);

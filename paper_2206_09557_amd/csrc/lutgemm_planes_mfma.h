@@ -8,7 +8,7 @@
 // accumulation is fp32), and the group's scale multiplies the accumulator once per group
 // (section 3.2 rule 2).  This is the alternative the paper's discussion of batch points to
 // (section 6: with growing batch the table lookups become the limit): its cost does not grow
-// with batch up to 16 vectors, so it overtakes the lookup path at a batch of four to seven
+// with batch up to 16 vectors, so it overtakes the lookup path at a batch of three to six
 // (small layers earlier).
 //
 // Work split: a workgroup owns a row range and a K group (a run of K tiles) and keeps the

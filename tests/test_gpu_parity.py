@@ -199,11 +199,11 @@ def test_mfma_path_rejects_groups_not_multiple_of_64():
 
 def test_auto_path_is_one_of_the_two():
     # LUTGEMM_PATH_AUTO: by shape and batch alone, the matrix-core path from five vectors on
-    # (four on small layers) where it applies, else the lookup path; bit for bit that path's y
+    # (three on small layers) where it applies, else the lookup path; bit for bit that path's y
     m, n, q = 300, 2048, 3
     W = synth.weights_fp16(m, n, seed=5600)
-    for g, batch, want_mfma in [(128, 8, True), (128, 5, True), (128, 4, True), (128, 3, False), (128, 1, False),
-                                (32, 8, False), (0, 6, True)]:
+    for g, batch, want_mfma in [(128, 8, True), (128, 5, True), (128, 4, True), (128, 3, True), (128, 2, False),
+                                (128, 1, False), (32, 8, False), (0, 6, True)]:
         print(f"case g={g} batch={batch}", flush=True)
         p = Packed.from_weights(W, q, g, MODES["greedy_z"])
         X = synth.activations_fp16(n, seed=5601 + batch, batch=batch)
