@@ -1114,9 +1114,11 @@ void choose_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
 }
 
 // The same choice for the pair kernel (NT counts half tiles).  Costs in units of one round
-// of units of a workgroup: a table build is worth about 1.75 of them; the final reduction
+// of units of a workgroup: a table build is worth about 2.5 of them; the final reduction
 // runs in batches (rows of a range per pass of the workgroup x 16 K groups x 2 vectors) of
-// about 1.25 each, which is what rules out one half tile per group on wide layers.
+// about 1.25 each, and more than 16 K groups cost further batches and more partial sums
+// (1 plus 0.1 per group beyond 16), which is what rules out one half tile per group on wide
+// layers.
 void choose_pair_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
   double best = 1e30;
   const int max_rs = (RB + kWaves - 1) / kWaves;
@@ -1129,7 +1131,7 @@ void choose_pair_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
     const int rounds = (blocks + kWaves - 1) / kWaves;
     const int tiles = (NT + kg - 1) / kg;
     const int passes = (blocks * 16 + rows_per_pass - 1) / rows_per_pass;
-    const double cost = tiles * (rounds + 1.75) + 1.25 * 2 * passes * ((kg + 15) / 16);
+    const double cost = tiles * (rounds + 2.5) + 1.25 * 2 * passes * ((kg + 15) / 16) + (kg > 16 ? 1.0 + 0.1 * (kg - 16) : 0.0);
     if (cost < best) {
       best = cost;
       *KG = kg;
