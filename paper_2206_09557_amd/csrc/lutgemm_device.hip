@@ -1220,7 +1220,9 @@ GemvKernel pick_planes_kernel(int q, bool has_z, int batch) {
 // Grid of the matrix-core kernel: K groups x row ranges.  A wavefront keeps the outputs of at
 // most kPlanesMaxUnits row blocks in registers, which bounds the row range; few K groups keep
 // the split-K partials (batch x rows x 4 bytes per group, written and read back) small
-// against the weights.  Costs in microseconds, from measurement on the FC1 shape.
+// against the weights.  Costs in microseconds, from measurement on the OPT-175B shapes: 2.7 per
+// unit, 1.5 per tile, 6 per pass of workgroups over the device (sign table, first X tile,
+// start-up), 5 TB/s for the partials, 3 for the final reduction.
 void plan_planes_grid(int cus, int waves, int batch, GemvParams* p) {
   const int slots = cus > 256 ? 256 : cus;
   const int min_rs = (p->RB + kPlanesMaxUnits * waves - 1) / (kPlanesMaxUnits * waves);
@@ -1235,7 +1237,7 @@ void plan_planes_grid(int cus, int waves, int batch, GemvParams* p) {
     const int units = (blocks + waves - 1) / waves;
     const int rounds = (kg * rs + slots - 1) / slots;           // passes of workgroups over the device
     const double partial_mb = kg > 1 ? (double)kg * p->RB * 16 * batch * 8 / 1e6 : 0.0;
-    const double cost = rounds * (tpg * (units * 2.7 + 1.5)) + partial_mb / 5.0 + (kg > 1 ? 3.0 : 0.0);
+    const double cost = rounds * (tpg * (units * 2.7 + 1.5) + 6.0) + partial_mb / 5.0 + (kg > 1 ? 3.0 : 0.0);
     if (cost < best) {
       best = cost;
       p->KG = kg;
