@@ -1153,7 +1153,9 @@ void choose_quad_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
     int rs = cus / kg;
     rs = rs < 1 ? 1 : (rs > max_rs ? max_rs : rs);
     const int units = (pairs + rs - 1) / rs;
-    const int rounds = (units + kWaves - 1) / kWaves;
+    // (fractional beyond the first: the queue lets the wavefronts of a workgroup share a last,
+    // partly filled round)
+    const double rounds = units > kWaves ? (double)units / kWaves : 1.0;
     const int tiles = (NT + kg - 1) / kg;
     const int passes = (units * 32 + rows_per_pass - 1) / rows_per_pass;
     const double cost = tiles * (rounds + 1.75) + 1.25 * 4 * passes * ((kg + 15) / 16);
