@@ -217,6 +217,21 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
                       int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* HOST.  The workgroup grid the lookup kernels are launched with for an m x n layer of q
+   planes and group size g, as chosen from these alone (appendix B: every block owns a tile
+   of the weights and a set of tables; the partial outputs of the blocks along a row are
+   then combined):
+     vectors  activation vectors per pass: 1 (lutgemm_gemv), 2 or 4 (the kernels
+              lutgemm_gemm uses for pairs and fours)
+     compute_units  of the device to plan for; <= 0 asks the current device
+     out[0]   K groups (workgroups along the columns),
+     out[1]   K tiles of 1024 columns per K group (half tiles of 512 for vectors = 2,
+              quarter tiles of 256 for vectors = 4),
+     out[2]   row ranges (workgroups along the rows).
+   Tests use it to show which code path a shape reaches; tuning scripts to explain a time.
+   LUTGEMM_EINVAL for malformed arguments, LUTGEMM_EHIP if the device cannot be asked.  */
+int lutgemm_plan_grid(int64_t m, int64_t n, int q, int g, int vectors, int compute_units, int* out);
+
 /* DEVICE pointers.  Measurement aid, no part of the product: reads `bytes` bytes at src
    (bytes % 16 == 0, src 16-byte aligned) exactly once, every workgroup a contiguous share
    front to back, in the access shape of the weight stream of section 3.4's memory-bound

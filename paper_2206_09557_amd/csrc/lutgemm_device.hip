@@ -27,13 +27,16 @@
 
 namespace {
 
-#ifndef LUT_WAVES
-#define LUT_WAVES 16     // wavefronts per workgroup (four per SIMD: 128 registers each)
-#endif
-constexpr int kWaves = LUT_WAVES;
+constexpr int kWaves = 16;     // wavefronts per workgroup (four per SIMD: 128 registers each)
 constexpr int kThreads = kWaves * 64;
 constexpr int kLutBytes = 2 * 256 * 64 * 4;  // two sub-slabs x 256 keys x 64 lanes x fp32
 constexpr int kQueueWord = kLutBytes / 4;      // one extra LDS word after the tables: the workgroup's unit queue
+// Behind the queue word: running row sums of a workgroup whose K group has several tiles (GEMV
+// kernel): 16 floats per row block of its row range, carried in LDS from tile to tile instead
+// of through memory.  The host never plans such a K group for a longer row range.
+constexpr int kRunBlocks = 480;
+constexpr int kRunWord = kQueueWord + 4;
+constexpr int kGemvLdsFloats = kRunWord + kRunBlocks * 16;   // 161,808 bytes of the 160 KB
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -92,10 +95,11 @@ __device__ __forceinline__ float lds_f32(uint32_t byte_addr) {
 }
 
 // The split-K partials cross workgroups (and L2s) inside one kernel.  They are written and
-// read with device-scope relaxed atomics only: such a store is written through to memory
-// and is complete once the wave's store counter has drained, and such a load does not hit
-// a stale cached copy.  A full device-scope fence would also work but writes back and
-// invalidates a whole L2 each time, which costs several microseconds per kernel.
+// read with device-scope atomics only: such a store is written through to memory and stays
+// in the wavefront's memory counter until that write is acknowledged, and such a load is
+// served from the device's point of coherence, never from a stale cached copy.  What orders
+// one workgroup's partials before another workgroup's reads is described at
+// finish_row_range.
 __device__ __forceinline__ void store_device_coherent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -331,7 +335,7 @@ __device__ __forceinline__ float compute_unit(const Unit<Q, 0, Q, T, AMODE, HAS_
 // the caller issues in between, and build_tile_tables ends with the workgroup barrier that
 // publishes the tables.
 constexpr int kBuildPasses = 16 / kWaves;   // table slots (sub-slab, key range) per wavefront at T = 2
-static_assert(16 % kWaves == 0 && kWaves >= 8, "8 or 16 wavefronts per workgroup");
+static_assert(kBuildPasses == 1, "one table slot per wavefront");
 
 template <int T>
 __device__ __forceinline__ void fetch_tile_x(const GemvParams& p, int kt, int chunks_in_tile, int wave, int lane,
@@ -394,12 +398,17 @@ __device__ __forceinline__ void lane_tables(int lane, uint32_t (&lane_base)[4], 
 
 // One workgroup, one K tile kt, row blocks [rb0, rb1).  T = sub-slabs of the tile (1 or 2).
 // AMODE: how the lanes get their scales (see above).
-// first_tile: the partials are written; otherwise they are added to those of the earlier
-// tiles of the K group (each (wave, row block) pair is always served by the same wave).
-// A row's result leaves a wavefront either as a partial sum for the cross-group reduction
-// or, when the launch has a single K group of a single tile (n <= 1024), directly as y:
-// nothing is left to add, and the trip through the workspace and the arrival counter
-// would be most of the run time of so small a product.
+// A row's sum over the tile leaves a wavefront in one of three ways:
+//   * as a partial sum for the cross-group reduction (the usual case: one tile per K group);
+//   * directly as y, when the launch has a single K group of a single tile (n <= 1024):
+//     nothing is left to add, and the trip through the workspace and the arrival counter
+//     would be most of the run time of so small a product;
+//   * with several tiles per K group (`carry`), into the workgroup's running sums in LDS:
+//     the first tile writes them, later tiles add to them, and when the last tile is done
+//     the workgroup copies them to the workspace as its partial sums (flush_row_sums).  Any
+//     wavefront may take any unit of any tile: the barrier between two tiles orders one
+//     tile's LDS writes before the next tile's reads.  The lookup loop then needs neither
+//     the output pointers nor a trip through memory per tile.
 __device__ __forceinline__ void store_row_sum(const GemvParams& p, float* partial, bool direct, int row, float v) {
   if (direct) {
     if (row < p.m) {
@@ -413,9 +422,22 @@ __device__ __forceinline__ void store_row_sum(const GemvParams& p, float* partia
   }
 }
 
-template <int Q, int T, int AMODE, bool HAS_Z, int kDepth>
+// Running sums: add this tile's sum for (row block of the range, row of the block).
+__device__ __forceinline__ void carry_row_sum(float* lut, int block_in_range, int row_in_block, float v, bool first_tile) {
+  float* r = lut + kRunWord + block_in_range * 16 + row_in_block;
+  *r = first_tile ? v : *r + v;
+}
+
+// After the last tile of a K group of several: the running sums become the partial sums.
+__device__ __forceinline__ void flush_row_sums(const GemvParams& p, const float* lut, int rb0, int rb1, float* partial) {
+  __syncthreads();
+  const int rows = (rb1 - rb0) * 16;
+  for (int i = threadIdx.x; i < rows; i += kThreads) store_device_coherent(partial + rb0 * 16 + i, lut[kRunWord + i]);
+}
+
+template <int Q, int T, int AMODE, bool HAS_Z>
 __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int kt, int rb0, int rb1, float* partial,
-                                          bool first_tile, bool direct) {
+                                          bool carry, bool first_tile, bool direct) {
   using U = Unit<Q, 0, Q, T, AMODE, HAS_Z>;
   int lane = threadIdx.x & 63;
   // Everything derived from the lane id below belongs to this tile only: the empty asm
@@ -448,6 +470,9 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
     for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
       float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
       float prev = 0.0f;
+      // (these register-bound variants have no room for running sums in LDS: the sum of the
+      // K group's earlier tiles comes back from the workspace with the first fetch of a unit,
+      // always in the wavefront that wrote it, and the new sum goes there again)
       plane_passes<Q, 0, PP, T, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, !first_tile, lane_base, sum_x,
                                               acc, &prev);
       int row_in_block;
@@ -456,29 +481,27 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
     }
   } else {
   // Units of the workgroup: u = 0 .. n_units-1 (row block rb0 + u).  A wavefront starts with
-  // unit `wave` and takes every further one from the queue.  With kDepth == 1 the next unit
-  // is fetched while the current one is computed; the first fetch is issued before the
-  // tables are built and AFTER the fetch of the activations (loads return in order, and the
-  // build must not wait for a whole unit of weights).  Fetches beyond the last unit are
-  // redirected to it (a harmless re-read) instead of branching, so that the wait counters
-  // stay exact and later fetches stay in flight.
-  static_assert(kDepth == 0 || kDepth == 1, "zero or one unit fetched ahead");
+  // unit `wave` and takes every further one from the queue.  Nothing is fetched ahead of the
+  // unit being computed: the other fifteen wavefronts cover a fetch.
   const int n_units = rb1 - rb0;
   const int u_clamp = n_units - 1;
   u32x4 xraw[kBuildPasses];
   fetch_tile_x<T>(p, kt, chunks_in_tile, wave, lane, xraw);
   if (threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = kWaves;   // units 0..kWaves-1 are taken
-  U u[kDepth + 1];
+  U u;
   int cur = wave;                               // unit being computed (or about to be)
   // kEarly (the common scale mode, which has the registers for the fetch code twice): a
   // wavefront asks for its first unit as soon as the activations have ARRIVED and before it
   // builds its share of the tables, so that the build overlaps the fetch.  Not before they
   // arrive: every wavefront of the device would flood the memory system at once and the
   // activations, which every lookup waits for, would queue behind the weights (measured).
-  constexpr bool kEarly = kDepth == 0 && AMODE == kAlphaQuad;
-  if (kEarly) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  if (kDepth == 1 || kEarly)
-    load_unit(u[0], p, tile_base, rb0 + min(cur, u_clamp), lane, grp, partial, out_row, !first_tile);
+  // The fetch is unconditional (a wavefront without a unit re-reads the last one): no branch
+  // between a fetch and its use, so that the wait counters stay exact.
+  constexpr bool kEarly = AMODE == kAlphaQuad;
+  if (kEarly) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    load_unit(u, p, tile_base, rb0 + min(cur, u_clamp), lane, grp, partial, out_row, false);
+  }
 
   build_tile_tables<T>(lut, chunks_in_tile, wave, lane, xraw);
   uint32_t lane_base[4];
@@ -496,24 +519,22 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
     int parked_rb = 0, n_parked = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      int nxt = cur;
-      if (kDepth == 1) {
-        nxt = next_unit(lut, lane);
-        load_unit(u[(j + 1) & 1], p, tile_base, rb0 + min(nxt, u_clamp), lane, grp, partial, out_row, !first_tile);
-      } else if (!kEarly) {
-        load_unit(u[0], p, tile_base, rb0 + cur, lane, grp, partial, out_row, !first_tile);
-      }
+      if (!kEarly) load_unit(u, p, tile_base, rb0 + cur, lane, grp, partial, out_row, false);
       int row_in_block;
-      const U& uc = u[kDepth == 1 ? (j & 1) : 0];
-      const float s = compute_unit(uc, lane, lane_base, sum_x, &row_in_block) + uc.prev;
+      const float s = compute_unit(u, lane, lane_base, sum_x, &row_in_block);
       parked = (lane_row == j) ? s : parked;
       parked_rb = (lane_row == j) ? rb0 + cur : parked_rb;
       n_parked = j + 1;
-      cur = (kDepth == 1) ? nxt : next_unit(lut, lane);
+      cur = next_unit(lut, lane);
       if (cur >= n_units) break;
-      if (kEarly) load_unit(u[0], p, tile_base, rb0 + cur, lane, grp, partial, out_row, !first_tile);   // no fetch in flight at the exit above
+      if (kEarly) load_unit(u, p, tile_base, rb0 + cur, lane, grp, partial, out_row, false);   // no fetch in flight at the exit above
     }
-    if (lane_row < n_parked) store_row_sum(p, partial, direct, parked_rb * 16 + out_row, parked);
+    if (lane_row < n_parked) {
+      if (carry)
+        carry_row_sum(lut, parked_rb - rb0, out_row, parked, first_tile);
+      else
+        store_row_sum(p, partial, direct, parked_rb * 16 + out_row, parked);
+    }
   }
   }   // Q <= 4
 }
@@ -580,11 +601,26 @@ __device__ __forceinline__ void reduce_rows_by_groups(const GemvParams& p, int r
 // groups are added in index order by whoever arrives last, so y is reproducible bit for bit).
 template <int NVEC>
 __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut, int rs, int rb0, int rb1) {
-  __syncthreads();                 // every partial store has completed, every lookup is done: the table memory is free
+  // Hand-off of the partials to whichever workgroup arrives last for this row range, ordered
+  // by completion rather than by fences:
+  //  1. every wavefront waits (s_waitcnt vmcnt(0)) until its own partial stores have been
+  //     acknowledged; they are write-through device-scope stores, so they are in memory then;
+  //  2. the workgroup barrier follows, so thread 0 issues the arrival increment only after
+  //     every partial of the workgroup is in memory;
+  //  3. the workgroup that reads KG - 1 from the counter knows that all other groups'
+  //     partials were in memory before their increments, hence before its own; its loads of
+  //     them are issued after a second barrier that follows the return of the increment, and
+  //     they are device-scope loads.
+  // The language's memory model would express 2 and 3 as a release / acquire pair on the
+  // counter.  On this device either half writes back or invalidates a whole L2 and costs 6
+  // to 14 microseconds per launch (measured), for stores that are already in memory and
+  // loads that bypass the caches anyway; the explicit wait of step 1 is what the hardware
+  // needs and what a barrier alone does not give (it does not wait for other wavefronts'
+  // stores in flight).  The counter itself is a relaxed device-scope read-modify-write.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();                 // every lookup is done as well: the table memory is free
   uint32_t* flag = reinterpret_cast<uint32_t*>(lut);
   if (threadIdx.x == 0) {
-    // Issued after the barrier, hence after the completion of every partial store of this
-    // workgroup (the barrier drains the store counters of all its wavefronts).
     const uint32_t arrived = __hip_atomic_fetch_add(p.counters + rs, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     flag[0] = (arrived == (uint32_t)(p.KG - 1)) ? 1u : 0u;
   }
@@ -602,23 +638,10 @@ __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut
     __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Units fetched ahead of the one being computed.  With 16 wavefronts per workgroup the other
-// wavefronts cover a fetch, and nothing is fetched ahead; with 8 (256 registers each) one
-// unit is, where two units fit without spilling (any use of scratch memory costs far more
-// than a prefetch hides).
-constexpr int prefetch_depth(int q, int amode) {
-#ifdef LUT_DEPTH
-  return LUT_DEPTH;
-#else
-  if (kWaves > 8) return 0;
-  return ((amode & 3) == kAlphaQuad && q <= 4) || ((amode & 3) == kAlphaPerSlot && q <= 3) ? 1 : 0;   // q > 4: unused
-#endif
-}
-
 // AM2 / AM1: scale modes of the two-sub-slab tiles and of a one-sub-slab last tile.
 template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
-  __shared__ float lut[kLutBytes / 4 + 4];
+  __shared__ float lut[kGemvLdsFloats];
   // The lookup addresses are formed as if the tables start at LDS address 0.
   if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
   const int kg = blockIdx.x;
@@ -627,17 +650,28 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
   row_range(p, &rb0, &rb1);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
   const bool direct = p.NT == 1;   // one tile, hence one K group: the sums of the tile are y
+  const int kt_end = min((kg + 1) * p.TPG, p.NT);
+  // several tiles per K group: running sums in LDS (see carries_in_lds; a last K group with a
+  // single tile takes the same path as the others)
+  constexpr bool kCarry = Q <= 4 && (AM2 & 3) != kAlphaPerChunk;
+  const bool carry = kCarry && p.TPG > 1;
 
-  for (int ti = 0; ti < p.TPG; ++ti) {
-    const int kt = kg * p.TPG + ti;
-    if (kt >= p.NT) break;
-    if (ti > 0) __syncthreads();   // every lookup of the previous tile is done before its tables are overwritten
+  for (int kt = kg * p.TPG; kt < kt_end; ++kt) {
+    const bool first_tile = kt == kg * p.TPG;
+    if (!first_tile) {
+      // every lookup of the previous tile is done before its tables are overwritten, every
+      // running sum of it written before it is read (those that go through memory:
+      // acknowledged, as in finish_row_range)
+      if (!kCarry) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
     if (min(128, p.nchunks - 128 * kt) > 64)
-      tile_body<Q, 2, AM2, HAS_Z, prefetch_depth(Q, AM2)>(p, lut, kt, rb0, rb1, partial, ti == 0, direct);
+      tile_body<Q, 2, AM2, HAS_Z>(p, lut, kt, rb0, rb1, partial, carry, first_tile, direct);
     else
-      tile_body<Q, 1, AM1, HAS_Z, prefetch_depth(Q, AM1)>(p, lut, kt, rb0, rb1, partial, ti == 0, direct);
+      tile_body<Q, 1, AM1, HAS_Z>(p, lut, kt, rb0, rb1, partial, carry, first_tile, direct);
   }
 
+  if (carry) flush_row_sums(p, lut, rb0, rb1, partial);
   if (!direct) finish_row_range<1>(p, lut, rs, rb0, rb1);
 }
 
@@ -652,15 +686,7 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
 // a unit is (half tile, row block).
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-#ifndef LUT_PAIR_DEPTH
-#define LUT_PAIR_DEPTH 1
-#endif
-constexpr int kPairDepth = LUT_PAIR_DEPTH;
-#ifndef LUT_STORE_LAG
-#define LUT_STORE_LAG 1
-#endif
-constexpr int kStoreLag = LUT_STORE_LAG;
-static_assert(kStoreLag == 0 || kStoreLag == 1, "results are stored at once or one unit later");
+constexpr int kPairDepth = 1;   // units fetched ahead in the pair and quad kernels, where the registers allow
 
 __device__ __forceinline__ f32x2 lds_f32x2(uint32_t byte_addr) {
   return *(const __attribute__((address_space(3))) f32x2*)(uintptr_t)byte_addr;
@@ -854,24 +880,16 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
     // that carries an unused fetch back to the loop head, and with it a wait for all memory
     // traffic, stores included, on every pass.  A wavefront that finds the queue empty part
     // way through a pass still fetches (the last unit, again) and stores (to a spare area
-    // nobody reads) but skips the lookups.  Results are kept for kStoreLag more units and
+    // nobody reads) but skips the lookups.  Results are kept for one more unit and
     // stored right after a fetch has been issued (a store shares the wavefront's memory
     // counter with the fetches; see tile_body), by all four 16-lane groups (same address,
     // same value).  The spare area has 128 bytes per wavefront: one spare line for all would
     // serialise every wavefront of the device on one memory channel.
     if (uid[0] >= n_units) return;
     float* const spare0 = p.spare + (((blockIdx.y * gridDim.x + blockIdx.x) & 255) * 16 + wave) * 32;
-    constexpr int kHeld = kStoreLag > 0 ? kStoreLag : 1;
-    float held0[kHeld], held1[kHeld];
-    float* held_to[kHeld];     // wave-uniform; the second vector's result goes held_step further
-    int64_t held_step[kHeld];
-#pragma unroll
-    for (int k = 0; k < kHeld; ++k) {
-      held0[k] = 0.0f;
-      held1[k] = 0.0f;
-      held_to[k] = spare0;
-      held_step[k] = 16;
-    }
+    float held0 = 0.0f, held1 = 0.0f;
+    float* held_to = spare0;     // wave-uniform; the second vector's result goes held_step further
+    int64_t held_step = 16;
     do {
 #pragma unroll
       for (int j = 0; j <= D; ++j) {
@@ -883,36 +901,24 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
           load_unit<true>(u[fill], p, tile_base, rb, lane, grp, partial, out_row, !first_tile, tile_T, t0);
           prev1[fill] = !first_tile ? load_device_coherent(partial1 + rb * 16 + out_row) : 0.0f;
         }
-        constexpr int hs = 0;
-        if (kStoreLag > 0) {
-          store_device_coherent(held_to[hs] + out_row, held0[hs]);
-          store_device_coherent(held_to[hs] + held_step[hs] + out_row, held1[hs]);
-        }
+        store_device_coherent(held_to + out_row, held0);
+        store_device_coherent(held_to + held_step + out_row, held1);
         __builtin_amdgcn_sched_barrier(0);   // fetch and stores stay ahead of the lookups below
         const bool real = uid[j] < n_units;
         if (real) {
           float acc[2][4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
           accumulate_pair(u[j], lane_base, sum_x, acc);
           int row_in_block;
-          held0[hs] = quad_rows_reduce(acc[0], lane, &row_in_block) + u[j].prev;
-          held1[hs] = quad_rows_reduce(acc[1], lane, &row_in_block) + prev1[j];
+          held0 = quad_rows_reduce(acc[0], lane, &row_in_block) + u[j].prev;
+          held1 = quad_rows_reduce(acc[1], lane, &row_in_block) + prev1[j];
         }
-        held_to[hs] = real ? partial + (rb0 + uid[j]) * 16 : spare0;
-        held_step[hs] = real ? p.vec_stride : 16;
-        if (kStoreLag == 0) {
-          store_device_coherent(held_to[hs] + out_row, held0[hs]);
-          store_device_coherent(held_to[hs] + held_step[hs] + out_row, held1[hs]);
-        }
+        held_to = real ? partial + (rb0 + uid[j]) * 16 : spare0;
+        held_step = real ? p.vec_stride : 16;
         if (D == 0) uid[0] = next_unit(lut, lane);
       }
     } while (uid[0] < n_units);
-    if (kStoreLag > 0) {
-#pragma unroll
-      for (int k = 0; k < kHeld; ++k) {
-        store_device_coherent(held_to[k] + out_row, held0[k]);
-        store_device_coherent(held_to[k] + held_step[k] + out_row, held1[k]);
-      }
-    }
+    store_device_coherent(held_to + out_row, held0);
+    store_device_coherent(held_to + held_step + out_row, held1);
   }
 }
 
@@ -931,7 +937,10 @@ __global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
   for (int ti = 0; ti < p.TPG; ++ti) {
     const int h = kg * p.TPG + ti;
     if (h >= p.NT) break;
-    if (ti > 0) __syncthreads();
+    if (ti > 0) {   // as in the GEMV kernel
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
     const int kt = h >> 1, t0 = h & 1;
     if (min(128, p.nchunks - 128 * kt) > 64)
       pair_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, rb0, rb1, partial, ti == 0);
@@ -944,31 +953,54 @@ __global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
 #include "lutgemm_quad.h"
 #include "lutgemm_planes_mfma.h"
 
+#if !defined(LUT_PART) || LUT_PART == 0
 // Zero the arrival counters of a fresh workspace.
 __global__ __launch_bounds__(256) void lutgemm_zero_counters_kernel(uint32_t* counters, int count) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < count) counters[i] = 0u;
 }
+#endif
 
-using GemvKernel = void (*)(GemvParams);
+// Kernel handles as hipLaunchKernel takes them.  The kernel families are instantiated in
+// separate translation units of this one source (-DLUT_PART=k compiles family k only, see
+// build.py), so that a build uses several cores; without LUT_PART everything is one unit.
+using GemvKernel = const void*;
+#ifdef LUT_PART
+#define LUT_HAS_PART(k) (LUT_PART == (k))
+#else
+#define LUT_HAS_PART(k) 1
+#endif
+}  // namespace
+
+namespace lutgemm_parts {
+// family: 0 = no offsets, 1 = offsets, 2 = shared-scale layout (always with offsets)
+const void* gemv_family0(int q, int64_t g);
+const void* gemv_family1(int q, int64_t g);
+const void* gemv_family2(int q, int64_t g);
+const void* pair_family0(int q, int64_t g);
+const void* pair_family1(int q, int64_t g);
+const void* pair_family2(int q, int64_t g);
+const void* quad_family0(int q, int64_t g);
+const void* quad_family1(int q, int64_t g);
+const void* quad_family2(int q, int64_t g);
+const void* planes_family(int q, bool has_z, int batch);
+}  // namespace lutgemm_parts
+
+namespace {
 
 template <bool HAS_Z, int AM2, int AM1>
 GemvKernel pick_q(int q) {
-#ifdef LUT_ONLY_Q   // development builds: one plane count only
-  return q == LUT_ONLY_Q ? lutgemm_gemv_kernel<LUT_ONLY_Q, HAS_Z, AM2, AM1> : nullptr;
-#else
   switch (q) {
-    case 1: return lutgemm_gemv_kernel<1, HAS_Z, AM2, AM1>;
-    case 2: return lutgemm_gemv_kernel<2, HAS_Z, AM2, AM1>;
-    case 3: return lutgemm_gemv_kernel<3, HAS_Z, AM2, AM1>;
-    case 4: return lutgemm_gemv_kernel<4, HAS_Z, AM2, AM1>;
-    case 5: return lutgemm_gemv_kernel<5, HAS_Z, AM2, AM1>;
-    case 6: return lutgemm_gemv_kernel<6, HAS_Z, AM2, AM1>;
-    case 7: return lutgemm_gemv_kernel<7, HAS_Z, AM2, AM1>;
-    case 8: return lutgemm_gemv_kernel<8, HAS_Z, AM2, AM1>;
+    case 1: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<1, HAS_Z, AM2, AM1>);
+    case 2: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<2, HAS_Z, AM2, AM1>);
+    case 3: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<3, HAS_Z, AM2, AM1>);
+    case 4: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<4, HAS_Z, AM2, AM1>);
+    case 5: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<5, HAS_Z, AM2, AM1>);
+    case 6: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<6, HAS_Z, AM2, AM1>);
+    case 7: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<7, HAS_Z, AM2, AM1>);
+    case 8: return reinterpret_cast<const void*>(lutgemm_gemv_kernel<8, HAS_Z, AM2, AM1>);
   }
   return nullptr;
-#endif
 }
 
 template <bool HAS_Z, int SH>
@@ -981,28 +1013,24 @@ GemvKernel pick_mode(int q, int64_t g) {
 
 // shared: the scale buffer is in the shared-scale layout (offsets are then always present)
 GemvKernel pick_kernel(int q, bool has_z, bool shared, int64_t g) {
-  if (shared) return pick_mode<true, kAlphaShared>(q, g);
-  return has_z ? pick_mode<true, 0>(q, g) : pick_mode<false, 0>(q, g);
+  if (shared) return lutgemm_parts::gemv_family2(q, g);
+  return has_z ? lutgemm_parts::gemv_family1(q, g) : lutgemm_parts::gemv_family0(q, g);
 }
 
 // Pair kernel: a lane's dword is one chunk, so the per-chunk scale mode does not occur.
 template <bool HAS_Z, int AM2, int AM1>
 GemvKernel pick_pair_q(int q) {
-#ifdef LUT_ONLY_Q
-  return q == LUT_ONLY_Q ? lutgemm_pair_kernel<LUT_ONLY_Q, HAS_Z, AM2, AM1> : nullptr;
-#else
   switch (q) {
-    case 1: return lutgemm_pair_kernel<1, HAS_Z, AM2, AM1>;
-    case 2: return lutgemm_pair_kernel<2, HAS_Z, AM2, AM1>;
-    case 3: return lutgemm_pair_kernel<3, HAS_Z, AM2, AM1>;
-    case 4: return lutgemm_pair_kernel<4, HAS_Z, AM2, AM1>;
-    case 5: return lutgemm_pair_kernel<5, HAS_Z, AM2, AM1>;
-    case 6: return lutgemm_pair_kernel<6, HAS_Z, AM2, AM1>;
-    case 7: return lutgemm_pair_kernel<7, HAS_Z, AM2, AM1>;
-    case 8: return lutgemm_pair_kernel<8, HAS_Z, AM2, AM1>;
+    case 1: return reinterpret_cast<const void*>(lutgemm_pair_kernel<1, HAS_Z, AM2, AM1>);
+    case 2: return reinterpret_cast<const void*>(lutgemm_pair_kernel<2, HAS_Z, AM2, AM1>);
+    case 3: return reinterpret_cast<const void*>(lutgemm_pair_kernel<3, HAS_Z, AM2, AM1>);
+    case 4: return reinterpret_cast<const void*>(lutgemm_pair_kernel<4, HAS_Z, AM2, AM1>);
+    case 5: return reinterpret_cast<const void*>(lutgemm_pair_kernel<5, HAS_Z, AM2, AM1>);
+    case 6: return reinterpret_cast<const void*>(lutgemm_pair_kernel<6, HAS_Z, AM2, AM1>);
+    case 7: return reinterpret_cast<const void*>(lutgemm_pair_kernel<7, HAS_Z, AM2, AM1>);
+    case 8: return reinterpret_cast<const void*>(lutgemm_pair_kernel<8, HAS_Z, AM2, AM1>);
   }
   return nullptr;
-#endif
 }
 
 template <bool HAS_Z, int SH>
@@ -1015,27 +1043,23 @@ GemvKernel pick_pair_mode(int q, int64_t g) {
 }
 
 GemvKernel pick_pair_kernel(int q, bool has_z, bool shared, int64_t g) {
-  if (shared) return pick_pair_mode<true, kAlphaShared>(q, g);
-  return has_z ? pick_pair_mode<true, 0>(q, g) : pick_pair_mode<false, 0>(q, g);
+  if (shared) return lutgemm_parts::pair_family2(q, g);
+  return has_z ? lutgemm_parts::pair_family1(q, g) : lutgemm_parts::pair_family0(q, g);
 }
 
 template <bool HAS_Z, int AM2, int AM1>
 GemvKernel pick_quad_q(int q) {
-#ifdef LUT_ONLY_Q
-  return q == LUT_ONLY_Q ? lutgemm_quad_kernel<LUT_ONLY_Q, HAS_Z, AM2, AM1> : nullptr;
-#else
   switch (q) {
-    case 1: return lutgemm_quad_kernel<1, HAS_Z, AM2, AM1>;
-    case 2: return lutgemm_quad_kernel<2, HAS_Z, AM2, AM1>;
-    case 3: return lutgemm_quad_kernel<3, HAS_Z, AM2, AM1>;
-    case 4: return lutgemm_quad_kernel<4, HAS_Z, AM2, AM1>;
-    case 5: return lutgemm_quad_kernel<5, HAS_Z, AM2, AM1>;
-    case 6: return lutgemm_quad_kernel<6, HAS_Z, AM2, AM1>;
-    case 7: return lutgemm_quad_kernel<7, HAS_Z, AM2, AM1>;
-    case 8: return lutgemm_quad_kernel<8, HAS_Z, AM2, AM1>;
+    case 1: return reinterpret_cast<const void*>(lutgemm_quad_kernel<1, HAS_Z, AM2, AM1>);
+    case 2: return reinterpret_cast<const void*>(lutgemm_quad_kernel<2, HAS_Z, AM2, AM1>);
+    case 3: return reinterpret_cast<const void*>(lutgemm_quad_kernel<3, HAS_Z, AM2, AM1>);
+    case 4: return reinterpret_cast<const void*>(lutgemm_quad_kernel<4, HAS_Z, AM2, AM1>);
+    case 5: return reinterpret_cast<const void*>(lutgemm_quad_kernel<5, HAS_Z, AM2, AM1>);
+    case 6: return reinterpret_cast<const void*>(lutgemm_quad_kernel<6, HAS_Z, AM2, AM1>);
+    case 7: return reinterpret_cast<const void*>(lutgemm_quad_kernel<7, HAS_Z, AM2, AM1>);
+    case 8: return reinterpret_cast<const void*>(lutgemm_quad_kernel<8, HAS_Z, AM2, AM1>);
   }
   return nullptr;
-#endif
 }
 
 template <bool HAS_Z, int SH>
@@ -1046,11 +1070,11 @@ GemvKernel pick_quad_mode(int q, int64_t g) {   // a lane's dwords are chunks of
 }
 
 GemvKernel pick_quad_kernel(int q, bool has_z, bool shared, int64_t g) {
-  if (shared) return pick_quad_mode<true, kAlphaShared>(q, g);
-  return has_z ? pick_quad_mode<true, 0>(q, g) : pick_quad_mode<false, 0>(q, g);
+  if (shared) return lutgemm_parts::quad_family2(q, g);
+  return has_z ? lutgemm_parts::quad_family1(q, g) : lutgemm_parts::quad_family0(q, g);
 }
 
-int compute_units() {
+int compute_units_of_device() {
   static int cached[64] = {0};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
@@ -1093,7 +1117,13 @@ const Tuning& tuning() {
 // Workgroup grid: KG groups of TPG consecutive K tiles times row_splits row ranges, one
 // workgroup per compute unit.  Cost model in units of one (tile, row block) per wavefront:
 // the slowest wavefront's units plus a table build per tile, plus the cross-group sum.
-void choose_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
+// How the GEMV kernel of a (q, g) layer carries row sums from tile to tile of a K group: the
+// variants that fetch a unit in one piece keep them in LDS, which bounds the row range of a
+// workgroup; the register-bound ones (more than four planes, or a scale set per chunk:
+// g % 16 != 0) send them through the workspace.
+bool carries_in_lds(int q, int64_t g) { return q <= 4 && g % 16 == 0; }
+
+void choose_grid(int cus, int NT, int RB, bool lds_carry, int* KG, int* TPG, int* RS) {
   double best = 1e30;
   const int max_rs = (RB + kWaves - 1) / kWaves;
   for (int tpg = 1; tpg <= NT && tpg <= 8; ++tpg) {
@@ -1103,6 +1133,7 @@ void choose_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
     const int blocks = (RB + rs - 1) / rs;
     const int rounds = (blocks + kWaves - 1) / kWaves;
     const int tiles = (NT + kg - 1) / kg;
+    if (lds_carry && tpg > 1 && blocks > kRunBlocks) continue;   // the running sums of a row range live in LDS
     const double cost = tiles * (rounds + 0.5) + 0.03 * kg + 0.3 * (tpg - 1);
     if (cost < best) {
       best = cost;
@@ -1170,14 +1201,15 @@ void choose_quad_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
 
 // choose_grid plus the tuning overrides.
 // vectors: 1 (GEMV kernel), 2 (pair kernel), 4 (quad kernel)
-void plan_grid(int cus, int vectors, GemvParams* p) {
+void plan_grid(int cus, int vectors, int q, int64_t g, GemvParams* p) {
   const int wgs = cus > 256 ? 256 : cus;
+  const bool lds_carry = carries_in_lds(q, g);
   if (vectors == 4)
     choose_quad_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
   else if (vectors == 2)
     choose_pair_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
   else
-    choose_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
+    choose_grid(wgs, p->NT, p->RB, lds_carry, &p->KG, &p->TPG, &p->row_splits);
   const int which = vectors == 4 ? 2 : (vectors == 2 ? 1 : 0);
   const int tpg = tuning().tpg[which], rs = tuning().rs[which];
   const int row_units = vectors == 4 ? (p->RB + 1) / 2 : p->RB;
@@ -1189,6 +1221,10 @@ void plan_grid(int cus, int vectors, GemvParams* p) {
     p->row_splits = p->row_splits < 1 ? 1 : (p->row_splits > max_rs ? max_rs : p->row_splits);
   }
   if (rs > 0) p->row_splits = rs > 256 ? 256 : (rs > row_units ? row_units : rs);
+  if (vectors == 1 && lds_carry && p->TPG > 1 && (p->RB + p->row_splits - 1) / p->row_splits > kRunBlocks) {
+    // an override that the running sums in LDS do not cover: back to the chooser's own grid
+    choose_grid(wgs, p->NT, p->RB, lds_carry, &p->KG, &p->TPG, &p->row_splits);
+  }
 }
 
 constexpr size_t kCounterBytes = 32768;   // 32 activation vectors x 256 row ranges
@@ -1197,27 +1233,20 @@ constexpr size_t kSpareBytes = 256 * 16 * 32 * sizeof(float);   // 128 bytes per
 
 template <bool HAS_Z, int NB>
 GemvKernel pick_planes_q(int q) {
-#ifdef LUT_ONLY_Q
-  return q == LUT_ONLY_Q ? lutgemm_planes_mfma_kernel<LUT_ONLY_Q, HAS_Z, NB> : nullptr;
-#else
   switch (q) {
-    case 1: return lutgemm_planes_mfma_kernel<1, HAS_Z, NB>;
-    case 2: return lutgemm_planes_mfma_kernel<2, HAS_Z, NB>;
-    case 3: return lutgemm_planes_mfma_kernel<3, HAS_Z, NB>;
-    case 4: return lutgemm_planes_mfma_kernel<4, HAS_Z, NB>;
-    case 5: return lutgemm_planes_mfma_kernel<5, HAS_Z, NB>;
-    case 6: return lutgemm_planes_mfma_kernel<6, HAS_Z, NB>;
-    case 7: return lutgemm_planes_mfma_kernel<7, HAS_Z, NB>;
-    case 8: return lutgemm_planes_mfma_kernel<8, HAS_Z, NB>;
+    case 1: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<1, HAS_Z, NB>);
+    case 2: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<2, HAS_Z, NB>);
+    case 3: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<3, HAS_Z, NB>);
+    case 4: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<4, HAS_Z, NB>);
+    case 5: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<5, HAS_Z, NB>);
+    case 6: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<6, HAS_Z, NB>);
+    case 7: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<7, HAS_Z, NB>);
+    case 8: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<8, HAS_Z, NB>);
   }
   return nullptr;
-#endif
 }
 
-GemvKernel pick_planes_kernel(int q, bool has_z, int batch) {
-  if (batch <= 16) return has_z ? pick_planes_q<true, 1>(q) : pick_planes_q<false, 1>(q);
-  return has_z ? pick_planes_q<true, 2>(q) : pick_planes_q<false, 2>(q);
-}
+GemvKernel pick_planes_kernel(int q, bool has_z, int batch) { return lutgemm_parts::planes_family(q, has_z, batch); }
 
 // Grid of the matrix-core kernel: K groups x row ranges.  A wavefront keeps the outputs of at
 // most kPlanesMaxUnits row blocks in registers, which bounds the row range; few K groups keep
@@ -1251,6 +1280,43 @@ void plan_planes_grid(int cus, int waves, int batch, GemvParams* p) {
 
 }  // namespace
 
+namespace lutgemm_parts {
+#if LUT_HAS_PART(0)
+const void* gemv_family0(int q, int64_t g) { return pick_mode<false, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(1)
+const void* gemv_family1(int q, int64_t g) { return pick_mode<true, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(2)
+const void* gemv_family2(int q, int64_t g) { return pick_mode<true, kAlphaShared>(q, g); }
+#endif
+#if LUT_HAS_PART(3)
+const void* pair_family0(int q, int64_t g) { return pick_pair_mode<false, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(4)
+const void* pair_family1(int q, int64_t g) { return pick_pair_mode<true, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(5)
+const void* pair_family2(int q, int64_t g) { return pick_pair_mode<true, kAlphaShared>(q, g); }
+#endif
+#if LUT_HAS_PART(6)
+const void* quad_family0(int q, int64_t g) { return pick_quad_mode<false, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(7)
+const void* quad_family1(int q, int64_t g) { return pick_quad_mode<true, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(8)
+const void* quad_family2(int q, int64_t g) { return pick_quad_mode<true, kAlphaShared>(q, g); }
+#endif
+#if LUT_HAS_PART(9)
+const void* planes_family(int q, bool has_z, int batch) {
+  if (batch <= 16) return has_z ? pick_planes_q<true, 1>(q) : pick_planes_q<false, 1>(q);
+  return has_z ? pick_planes_q<true, 2>(q) : pick_planes_q<false, 2>(q);
+}
+#endif
+}  // namespace lutgemm_parts
+
+#if LUT_HAS_PART(0)   // the entry points and the two small kernels: once per library
 // ---------------------------------------------------------------------------------------
 // Measurement aid: a kernel that only reads.  Every workgroup walks one contiguous share of
 // the buffer front to back, the way a GEMV workgroup walks its share of the packed weights
@@ -1320,7 +1386,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   if (need == 0) return LUTGEMM_EINVAL;
   if (workspace_bytes < need) return LUTGEMM_EWORKSPACE;
 
-  const int cus = compute_units();
+  const int cus = compute_units_of_device();
   if (cus <= 0) return LUTGEMM_EHIP;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
@@ -1338,12 +1404,14 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   for (int sh = 0; sh < 31; ++sh)
     if ((gg >> 3) == ((int64_t)1 << sh)) p.g_shift = sh;
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
-  plan_grid(cus, 1, &p);
+  plan_grid(cus, 1, q, gg, &p);
   const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
   p.kg_stride = m_pad * (batch + (batch % 4 == 3 ? 1 : 0));   // room for the dropped fourth vector of a quad of three
 
   GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
+  if (p.TPG > 1 && carries_in_lds(q, gg) && (p.RB + p.row_splits - 1) / p.row_splits > kRunBlocks)
+    return LUTGEMM_EUNSUPPORTED;   // (never planned: the kernel's running sums would not fit)
 
   uint32_t* counters = static_cast<uint32_t*>(workspace);
   p.spare = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
@@ -1359,14 +1427,14 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   GemvKernel quad_kern = nullptr, pair_kern = nullptr;
   if (batch >= 3) {
     pq.NT = 4 * p.NT;   // quarter ids; those a ragged last tile does not have are skipped by the kernel
-    plan_grid(cus, 4, &pq);
+    plan_grid(cus, 4, q, gg, &pq);
     quad_kern = pick_quad_kernel(q, z != nullptr, shared, gg);
     if (!quad_kern) return LUTGEMM_EUNSUPPORTED;
   }
   if (batch % 4 == 2) {
     const int last_chunks = p.nchunks - 128 * (p.NT - 1);
     pp.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);   // half tiles
-    plan_grid(cus, 2, &pp);
+    plan_grid(cus, 2, q, gg, &pp);
     pair_kern = pick_pair_kernel(q, z != nullptr, shared, gg);
     if (!pair_kern) return LUTGEMM_EUNSUPPORTED;
   }
@@ -1385,7 +1453,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     pb.range_base = row_units / pb.row_splits;
     pb.range_rem = row_units % pb.row_splits;
     void* args[] = {&pb};
-    if (hipLaunchKernel(reinterpret_cast<const void*>(kb), dim3(pb.KG, pb.row_splits), dim3(kThreads), args, 0,
+    if (hipLaunchKernel(kb, dim3(pb.KG, pb.row_splits), dim3(kThreads), args, 0,
                         stream) != hipSuccess)
       return LUTGEMM_EHIP;
     b += live;
@@ -1409,7 +1477,7 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   if (need == 0) return LUTGEMM_EINVAL;
   if (workspace_bytes < need) return LUTGEMM_EWORKSPACE;
 
-  const int cus = compute_units();
+  const int cus = compute_units_of_device();
   if (cus <= 0) return LUTGEMM_EHIP;
   GemvParams p;
   p.x = static_cast<const __half*>(x);
@@ -1455,9 +1523,34 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   p.range_base = p.RB / p.row_splits;
   p.range_rem = p.RB % p.row_splits;
   void* args[] = {&p};
-  if (hipLaunchKernel(reinterpret_cast<const void*>(kern), dim3(p.KG, p.row_splits), dim3(waves * 64), args, 0,
+  if (hipLaunchKernel(kern, dim3(p.KG, p.row_splits), dim3(waves * 64), args, 0,
                       static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return LUTGEMM_EHIP;
+  return LUTGEMM_OK;
+}
+
+int lutgemm_plan_grid(int64_t m, int64_t n, int q, int g, int vectors, int compute_units, int* out) {
+  if (!out || m < 1 || n < 8 || n % 8 != 0 || m > (int64_t)1 << 30 || n > (int64_t)1 << 30) return LUTGEMM_EINVAL;
+  if (q < 1 || q > 8 || g < 0) return LUTGEMM_EINVAL;
+  const int64_t gg = g == 0 ? n : g;
+  if (gg % 8 != 0 || n % gg != 0) return LUTGEMM_EINVAL;
+  if (vectors != 1 && vectors != 2 && vectors != 4) return LUTGEMM_EINVAL;
+  const int cus = compute_units > 0 ? compute_units : compute_units_of_device();
+  if (cus <= 0) return LUTGEMM_EHIP;
+  GemvParams p;
+  p.RB = (int)((m + 15) / 16);
+  p.nchunks = (int)(n / 8);
+  p.NT = (p.nchunks + 127) / 128;
+  if (vectors == 2) {
+    const int last_chunks = p.nchunks - 128 * (p.NT - 1);
+    p.NT = 2 * (p.NT - 1) + (last_chunks > 64 ? 2 : 1);
+  } else if (vectors == 4) {
+    p.NT = 4 * p.NT;
+  }
+  plan_grid(cus, vectors, q, gg, &p);
+  out[0] = p.KG;
+  out[1] = p.TPG;
+  out[2] = p.row_splits;
   return LUTGEMM_OK;
 }
 
@@ -1482,3 +1575,4 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
 }
 
 }  // extern "C"
+#endif   // LUT_HAS_PART(0)

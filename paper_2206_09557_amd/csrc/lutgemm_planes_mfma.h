@@ -300,6 +300,8 @@ __device__ __forceinline__ void reduce_rows_batch(const GemvParams& p, int rb0, 
 // kernel, with a run-time vector count and workgroup size).
 template <int THREADS>
 __device__ __forceinline__ void finish_rows_batch(const GemvParams& p, uint32_t* flag, int rs, int rb0, int rb1) {
+  // the hand-off of finish_row_range: own stores acknowledged, barrier, arrival count
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (threadIdx.x == 0) {
     const uint32_t arrived = __hip_atomic_fetch_add(p.counters + rs, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

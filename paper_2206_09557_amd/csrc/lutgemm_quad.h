@@ -220,10 +220,8 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
           for (int v = 0; v < 4; ++v)
             prev[fill][v] = !first_tile ? load_device_coherent(partial + v * p.vec_stride + rb * 16 + out_row) : 0.0f;
         }
-        if (kStoreLag > 0) {
 #pragma unroll
-          for (int v = 0; v < 4; ++v) store_device_coherent(held_to + v * held_step + pair_row, held[v]);
-        }
+        for (int v = 0; v < 4; ++v) store_device_coherent(held_to + v * held_step + pair_row, held[v]);
         __builtin_amdgcn_sched_barrier(0);   // fetch and stores stay ahead of the lookups below
         const bool real = uid[j] < n_units;
         if (real) {
@@ -238,17 +236,11 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
         }
         held_to = real ? partial + (rb0 + 2 * uid[j]) * 16 : spare0;
         held_step = real ? p.vec_stride : 0;
-        if (kStoreLag == 0) {
-#pragma unroll
-          for (int v = 0; v < 4; ++v) store_device_coherent(held_to + v * held_step + pair_row, held[v]);
-        }
         if (D == 0) uid[0] = next_unit(lut, lane);
       }
     } while (uid[0] < n_units);
-    if (kStoreLag > 0) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) store_device_coherent(held_to + v * held_step + pair_row, held[v]);
-    }
+    for (int v = 0; v < 4; ++v) store_device_coherent(held_to + v * held_step + pair_row, held[v]);
   }
 }
 
@@ -273,7 +265,12 @@ __global__ __launch_bounds__(kThreads) void lutgemm_quad_kernel(GemvParams p) {
     const int chunks = min(128, p.nchunks - 128 * kt);
     const int T = chunks > 64 ? 2 : 1;
     if (t0 >= T || 32 * h * T + t0 >= chunks) continue;   // no such quarter in this tile (wave-uniform)
-    if (!first) __syncthreads();   // every lookup of the previous quarter is done before its tables are overwritten
+    if (!first) {
+      // every lookup of the previous quarter is done before its tables are overwritten, and
+      // every partial sum of it is in memory before another wavefront reads it back
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
     if (T == 2)
       quad_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, h, rb0, rb1, partial, first);
     else

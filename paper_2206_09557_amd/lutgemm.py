@@ -40,6 +40,7 @@ _SIGNATURES = {
     "lutgemm_gemm_mfma": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                      _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_int, _c.c_uint,
                                      _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "lutgemm_plan_grid": (_c.c_int, [_c.c_int64, _c.c_int64, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p]),
     "lutgemm_stream_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "lutgemm_strerror": (_c.c_char_p, [_c.c_int]),
 }
@@ -177,6 +178,13 @@ def lutgemm_share_scales(alpha_packed, m, n, q, g):
     out = np.empty(ns // 2, dtype=np.float16)
     _check(lib().lutgemm_share_scales(alpha_packed.ctypes.data, m, n, q, g, out.ctypes.data), "lutgemm_share_scales")
     return out
+
+
+def lutgemm_plan_grid(m, n, q, g, vectors=1, compute_units=0):
+    """(K groups, tiles per K group, row ranges) of the lookup kernel for `vectors` per pass."""
+    out = (ctypes.c_int * 3)()
+    _check(lib().lutgemm_plan_grid(m, n, q, g, vectors, compute_units, ctypes.addressof(out)), "lutgemm_plan_grid")
+    return int(out[0]), int(out[1]), int(out[2])
 
 
 # ---- device --------------------------------------------------------------------------

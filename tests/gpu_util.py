@@ -84,23 +84,43 @@ def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, sha
     return y[0] if x16.ndim == 1 else y
 
 
+class RowBounds:
+    """Per-row error bounds of a layer: `l1` = sum_G g * (sum_i alpha[i][r][G] + |z[r][G]|), a
+    bound on the L1 norm of the dequantised row (the reading of "sum of alpha" that fp16
+    outputs can meet), and `strict` = max_G (sum_i alpha[i][r][G] + |z[r][G]|), the literal
+    reading, which the fp32 outputs are held to.  Indexing selects rows."""
+
+    def __init__(self, l1, strict):
+        self.l1, self.strict = l1, strict
+
+    def __getitem__(self, sel):
+        return RowBounds(self.l1[sel], self.strict[sel])
+
+
 def row_l1_bound(alpha, z, g_cols):
-    """Per-row bound sum_G g * (sum_i alpha[i][r][G] + |z[r][G]|) >= ||What_r||_1."""
+    """RowBounds from decoded scales alpha[q][m][NG] and offsets z[m][NG] (or None)."""
     s = np.abs(alpha.astype(np.float64)).sum(axis=0)
     if z is not None:
         s = s + np.abs(z.astype(np.float64))
-    return g_cols * s.sum(axis=1)
+    return RowBounds(g_cols * s.sum(axis=1), s.max(axis=1))
 
 
 def check_parity(y_gpu, y_ref, x16, rowbound, f32_out=False):
-    """The benchmark spec tolerances: relative L2 <= 1e-3 and max abs <= 1e-2 * |x|_inf * sum(alpha),
-    the sum read per row as a bound on the row's L1 norm; fp32 output is held to 1e-5."""
+    """Tolerances of the workload statement: relative L2 <= 1e-3 and max abs <=
+    1e-2 * |x|_inf * sum(alpha), the sum read per row as a bound on the row's L1 norm.
+    fp32 output is held to relative L2 <= 1e-5 and, element by element, to the literal
+    reading |y - y_ref| <= 1e-2 * |x|_inf * max_G sum_i alpha[i][r][G] (about 1e-3 on the
+    benchmark layers, far below any row's magnitude: a lost or stale partial sum fails it)."""
     y_gpu = np.asarray(y_gpu, dtype=np.float64)
     assert np.all(np.isfinite(y_gpu))
     rel = np.linalg.norm(y_gpu - y_ref) / max(np.linalg.norm(y_ref), 1e-30)
     assert rel <= (1e-5 if f32_out else 1e-3), f"relative L2 error {rel}"
     xinf = float(np.abs(np.asarray(x16, dtype=np.float64)).max())
-    bound = 1e-2 * xinf * rowbound
-    bad = np.abs(y_gpu - y_ref) > bound + 1e-30
+    err = np.abs(y_gpu - y_ref)
+    bad = err > 1e-2 * xinf * rowbound.l1 + 1e-30
     assert not bad.any(), f"max-abs bound broken at rows {np.flatnonzero(bad)[:8]}"
+    if f32_out:
+        bad = err > 1e-2 * xinf * rowbound.strict + 1e-30
+        assert not bad.any(), (f"strict per-element bound broken at rows {np.flatnonzero(bad)[:8]}: "
+                               f"errors {err[bad][:4]}, bounds {(1e-2 * xinf * rowbound.strict)[bad][:4]}")
     return rel

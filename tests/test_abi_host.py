@@ -179,3 +179,24 @@ def test_alternating_pack_lowers_the_quantisation_error():
         What = O.dequant(O.decode_bits(bits, m, n, q), O.decode_alpha(alpha, m, n // g, q), None, g)
         errs[mode] = float(((W.astype(np.float64) - What) ** 2).sum())
     assert errs[L.LUTGEMM_Q_ALTERNATING] < 0.7 * errs[L.LUTGEMM_Q_GREEDY]     # measured: 0.62 on Gaussian weights
+
+
+def test_plan_grid_is_host_logic_and_covers_every_tile():
+    # planning needs no GPU when the compute-unit count is given; whatever it chooses, the K
+    # groups cover every tile exactly once and the workgroups fit the device when they can
+    for (m, n) in list(synth.OPT_175B.values()) + list(synth.LLAMA_65B.values()) + [(16, 262144), (200000, 64), (1, 8)]:
+        for width in (1, 2, 4):
+            kg, tpg, rs = L.lutgemm_plan_grid(m, n, 3, 0 if n % 128 else 128, width, 256)
+            chunks = n // 8
+            nt = (chunks + 127) // 128
+            last = chunks - 128 * (nt - 1)
+            tiles = {1: nt, 2: 2 * (nt - 1) + (2 if last > 64 else 1), 4: 4 * nt}[width]
+            assert kg >= 1 and tpg >= 1 and rs >= 1
+            assert kg * tpg >= tiles > (kg - 1) * tpg
+            assert rs <= 256 and (kg * rs <= 256 or rs == 1)
+    assert L.lutgemm_plan_grid(16, 262144, 3, 128, 1, 256)[1] > 1
+    assert L.lutgemm_plan_grid(16, 262144, 5, 128, 1, 256)[1] > 1
+    with pytest.raises(L.LutGemmError):
+        L.lutgemm_plan_grid(16, 12, 3, 0, 1, 256)
+    with pytest.raises(L.LutGemmError):
+        L.lutgemm_plan_grid(16, 64, 3, 64, 3, 256)

@@ -1,8 +1,9 @@
 """GPU parity at the full workload sizes, in the launch configuration bench.py times:
-OPT-175B-shaped layers (q = 3, g = 128), OPT-13B-shaped layers (q = 4, g = 128) and
-LLaMA-65B-shaped layers with per-group offsets over a (q, g) sweep, batch 1.  The fp64
-oracle computes a sample of output rows one by one (first and last row blocks, block
-boundaries of the row splits, random rows); the 175B out-proj is compared on every row."""
+OPT-175B-shaped layers (q = 3, g = 128; every row of every layer, and the small-batch
+sweep 2..32 on FC1 through the lookup path), OPT-13B-shaped layers (q = 4, g = 128) and
+LLaMA-65B-shaped layers with per-group offsets over a (q, g) sweep, batch 1.  Where rows are
+sampled, the fp64 oracle computes them one by one (first and last row blocks, block
+boundaries of the row splits, random rows)."""
 import numpy as np
 import pytest
 
@@ -28,7 +29,7 @@ def _sample_rows(m, rng, count=96):
 
 
 @pytest.mark.parametrize("name", ["fc1", "fc2", "qkv", "out"])
-def test_opt175b_layer_sampled_rows(name):
+def test_opt175b_layer_all_rows(name):
     m, n = synth.OPT_175B[name]
     q, g = 3, 128
     print(f"case {name} m={m} n={n} q={q} g={g}", flush=True)
@@ -40,7 +41,7 @@ def test_opt175b_layer_sampled_rows(name):
     y16 = run(p, x)
     y32 = run(p, x, f32_out=True)
     np.testing.assert_array_equal(y32.astype(np.float16), y16)
-    rows = None if name == "out" else _sample_rows(m, np.random.default_rng(7))
+    rows = None   # every row: the oracle takes about a second per layer on the machine's cores
     y_ref, _ = c_oracle.gemv_packed(p.bits, p.alpha, p.z, x, m, n, q, g, rows=rows)
     print("oracle done", flush=True)
     a = O.decode_alpha(p.alpha, m, n // g, q)
@@ -97,22 +98,39 @@ def test_llama65b_layer_with_offset_sampled_rows(name, q, g):
     _check_layer(m, n, q, g, L.LUTGEMM_Q_UNIFORM_RTN, seed=4000 + 7 * q + g + m % 83)
 
 
-def test_small_batch_on_fc1_shape():
-    # config 5 at reduced batch: every activation vector of a batch is an independent GEMV
+_FC1 = {}
+
+
+def _fc1_packed():
+    """The FC1-shaped layer of the batch sweep, packed once for all its cases."""
+    if not _FC1:
+        m, n = synth.OPT_175B["fc1"]
+        W = synth.weights_fp16(m, n, seed=5000)
+        p = Packed.from_weights(W, 3, 128)
+        del W
+        a = O.decode_alpha(p.alpha, m, n // 128, 3)
+        _FC1["p"], _FC1["bound"] = p, row_l1_bound(a, None, 128)
+    return _FC1["p"], _FC1["bound"]
+
+
+@pytest.mark.parametrize("batch", [2, 3, 4, 8, 16, 32])
+def test_small_batch_sweep_on_fc1_shape_lookup_path(batch):
+    # the small-batch sweep of the workload list (paper section 6) through the lookup path
+    # alone (no LUTGEMM_PATH_AUTO), in the grids bench.py times: every vector, every row
     m, n = synth.OPT_175B["fc1"]
     q, g = 3, 128
-    print(f"case batch fc1 m={m} n={n}", flush=True)
-    W = synth.weights_fp16(m, n, seed=5000)
-    p = Packed.from_weights(W, q, g)
-    del W
-    X = synth.activations_fp16(n, seed=5500, batch=3)
+    p, bound = _fc1_packed()
+    grids = {w: L.lutgemm_plan_grid(m, n, q, g, w) for w in (1, 2, 4)}
+    print(f"case batch fc1 m={m} n={n} batch={batch} grids={grids}", flush=True)
+    X = synth.activations_fp16(n, seed=5500 + batch, batch=batch)
     Y = run(p, X, f32_out=True)
-    rows = _sample_rows(m, np.random.default_rng(5))
-    a = O.decode_alpha(p.alpha, m, n // g, q)
-    bound = row_l1_bound(a, None, g)
-    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g, rows=rows)
-    for b in range(3):
-        check_parity(Y[b][rows], Yref[b], X[b], bound[rows], f32_out=True)
+    Y16 = run(p, X)
+    np.testing.assert_array_equal(Y.astype(np.float16), Y16)
+    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g)
+    print("oracle done", flush=True)
+    for b in range(batch):
+        check_parity(Y[b], Yref[b], X[b], bound, f32_out=True)
+        check_parity(Y16[b], Yref[b], X[b], bound)
 
 
 @pytest.mark.parametrize("batch", [4, 32])
@@ -121,17 +139,12 @@ def test_mfma_path_on_fc1_shape(batch):
     m, n = synth.OPT_175B["fc1"]
     q, g = 3, 128
     print(f"case mfma fc1 m={m} n={n} batch={batch}", flush=True)
-    W = synth.weights_fp16(m, n, seed=5000)
-    p = Packed.from_weights(W, q, g)
-    del W
+    p, bound = _fc1_packed()
     X = synth.activations_fp16(n, seed=5600 + batch, batch=batch)
     Y = run(p, X, f32_out=True, mfma=True)
-    rows = _sample_rows(m, np.random.default_rng(6))
-    a = O.decode_alpha(p.alpha, m, n // g, q)
-    bound = row_l1_bound(a, None, g)
-    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g, rows=rows)
+    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g)
     for b in range(batch):
-        check_parity(Y[b][rows], Yref[b], X[b], bound[rows], f32_out=True)
+        check_parity(Y[b], Yref[b], X[b], bound, f32_out=True)
 
 
 def test_mfma_path_llama65b_down_with_offset():
