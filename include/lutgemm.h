@@ -191,6 +191,22 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
                  int q, int g, int mu, int64_t m, int64_t n, unsigned flags,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* For callers that cannot allocate device memory or pass a workspace along: code that runs
+   under HIP graph capture, tight serving loops, harnesses that forbid allocation.
+   lutgemm_gemv with the same arguments minus the workspace: the scratch memory is an array
+   of lutgemm_static_scratch_bytes() (8 MiB) inside the library's device image, one copy per
+   GPU, held until the process ends.  The call allocates nothing and never synchronises; the
+   first call on a device looks the array's address up and enqueues a small kernel that
+   zeroes its arrival counters.  LUTGEMM_EWORKSPACE if the layer needs more scratch than
+   the array holds (lutgemm_workspace_bytes(m, n, q, g, mu, 1) > 8 MiB: beyond about 2^21
+   weights-rows x K-tiles; the OPT-175B layers need 0.8 to 2.9 MiB).  All calls on one GPU
+   share that GPU's array, which keeps the last call's partial sums: calls must be ordered
+   on one stream (or otherwise not overlap); two that overlap race.  Same result, bit for
+   bit, as lutgemm_gemv.                                                                 */
+int lutgemm_gemv_static(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                        int q, int g, int mu, int64_t m, int64_t n, unsigned flags, void* hip_stream);
+size_t lutgemm_static_scratch_bytes(void);
+
 /* As lutgemm_gemv for `batch` activation vectors (1 <= batch <= 32): x is fp16
    [batch][n], y is [batch][m], workspace sized for this batch.  The vectors are taken four
    at a time; two or one left over have kernels of their own, three left over run as four

@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <mutex>
 
 #include "lutgemm.h"
 
@@ -1578,6 +1579,56 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   return lutgemm_gemm(x, bits, alpha, z, y, q, g, mu, m, n, 1, flags, workspace, workspace_bytes, hip_stream);
 }
+
+// ---------------------------------------------------------------------------------------
+// lutgemm_gemv for callers that cannot allocate: the workspace is a device array of this
+// library.  `static_scratch` below is a host-side stand-in for the device array, not a device
+// address: the address every device keeps of its own copy comes from hipGetSymbolAddress, once
+// per device, and only that address is ever handed to a kernel.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char static_scratch[kStaticScratchBytes];
+
+// Device address of this device's copy of the array (nullptr on error), looked up at the
+// first call on the device; that call also enqueues the zeroing of the arrival counters.
+static void* static_scratch_of_device(hipStream_t stream, int* rc) {
+  static std::mutex lock;
+  static void* address[64] = {nullptr};
+  *rc = LUTGEMM_OK;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    *rc = LUTGEMM_EHIP;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> guard(lock);
+  if (!address[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch)) != hipSuccess || !ptr) {
+      *rc = LUTGEMM_EHIP;
+      return nullptr;
+    }
+    // the counters start at zero (a small fill kernel, so that the call may be captured)
+    const int init = lutgemm_workspace_init(ptr, kStaticScratchBytes, stream);
+    if (init != LUTGEMM_OK) {
+      *rc = init;
+      return nullptr;
+    }
+    address[dev] = ptr;
+  }
+  return address[dev];
+}
+
+int lutgemm_gemv_static(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                        int q, int g, int mu, int64_t m, int64_t n, unsigned flags, void* hip_stream) {
+  const size_t need = lutgemm_workspace_bytes(m, n, q, g, mu, 1);
+  if (need == 0) return mu != 8 && m >= 1 && n >= 8 ? LUTGEMM_EUNSUPPORTED : LUTGEMM_EINVAL;
+  if (need > kStaticScratchBytes) return LUTGEMM_EWORKSPACE;   // the layer needs more than the array holds
+  int rc = LUTGEMM_OK;
+  void* scratch = static_scratch_of_device(static_cast<hipStream_t>(hip_stream), &rc);
+  if (!scratch) return rc;
+  return lutgemm_gemm(x, bits, alpha, z, y, q, g, mu, m, n, 1, flags, scratch, kStaticScratchBytes, hip_stream);
+}
+
+size_t lutgemm_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 }  // extern "C"
 #endif   // LUT_HAS_PART(0)

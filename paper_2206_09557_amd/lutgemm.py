@@ -34,6 +34,9 @@ _SIGNATURES = {
     "lutgemm_gemv": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                 _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_uint,
                                 _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "lutgemm_gemv_static": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                       _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_uint, _c.c_void_p]),
+    "lutgemm_static_scratch_bytes": (_c.c_size_t, []),
     "lutgemm_gemm": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                 _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_int, _c.c_uint,
                                 _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -195,6 +198,15 @@ def lutgemm_workspace_init(workspace, workspace_bytes, stream=0):
 def lutgemm_gemv(x, bits, alpha, z, y, q, g, mu, m, n, flags, workspace, workspace_bytes, stream=0):
     _check(lib().lutgemm_gemv(_addr(x), _addr(bits), _addr(alpha), _addr(z), _addr(y), q, g, mu, m, n, flags,
                               _addr(workspace), workspace_bytes, stream or None), "lutgemm_gemv")
+
+
+def lutgemm_gemv_static(x, bits, alpha, z, y, q, g, mu, m, n, flags, stream=0):
+    _check(lib().lutgemm_gemv_static(_addr(x), _addr(bits), _addr(alpha), _addr(z), _addr(y), q, g, mu, m, n, flags,
+                                     stream or None), "lutgemm_gemv_static")
+
+
+def lutgemm_static_scratch_bytes():
+    return lib().lutgemm_static_scratch_bytes()
 
 
 def lutgemm_gemm(x, bits, alpha, z, y, q, g, mu, m, n, batch, flags, workspace, workspace_bytes, stream=0):
