@@ -184,6 +184,39 @@ def main():
     avg_launch_bytes = total_bytes / nL
     achieved = avg_launch_bytes / (avg_launch_us * 1e-6) / 1e9
 
+    # ---- the same step as ONE grouped launch (lutgemm_gemv_group): the four products are
+    # independent here (each has its own input), so the workgroups of one layer may follow
+    # those of the previous one onto the device without a kernel boundary in between ----
+    ms, ns = [e["m"] for e in layers], [e["n"] for e in layers]
+    gwsb = L.lutgemm_group_workspace_bytes(ms, ns, Q, G)
+    gws = torch.empty(gwsb, dtype=torch.uint8, device="cuda")
+    L.lutgemm_workspace_init(gws, gwsb, sptr)
+    yg = [torch.empty(e["m"], dtype=torch.float16, device="cuda") for e in layers]
+    group_args = []
+    for c in range(max(e["copies"] for e in layers)):
+        group_args.append(([e["x"] for e in layers], [e["bits"][c % e["copies"]] for e in layers],
+                           [e["alpha"][c % e["copies"]] for e in layers]))
+
+    def launch_group(step):
+        xs, bs, als = group_args[step % len(group_args)]
+        L.lutgemm_gemv_group(xs, bs, als, None, yg, ms, ns, Q, G, MU, L.LUTGEMM_Y_F16, gws, gwsb, sptr)
+
+    for s in range(args.warmup + 3):
+        launch_group(s)
+    torch.cuda.synchronize()
+    group_ms = []
+    for r in range(args.regions):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for s in range(args.steps):
+            launch_group(r * args.steps + s)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        group_ms.append(ev0.elapsed_time(ev1) / args.steps)
+    group_equal = all(bool(torch.equal(a, e["y"])) for a, e in zip(yg, layers))
+    group_us = float(np.median(group_ms)) * 1e3
+
     # ---- per-layer breakdown, outside the timed regions: each shape alone, back to back,
     # rotating through its copies; then the same with ONE weight copy (whatever the last-level
     # cache keeps of it stays there between launches: "hot", not a figure a decoder sees,
@@ -295,6 +328,15 @@ def main():
         "stream_read_probe": {"gbs": round(stream_read_gbs, 1), "bytes": probe_bytes,
                               "kernel": "lutgemm_stream_read_kernel (read-only, 16 B per lane)"},
         "frac_of_stream_read": round(step_gbs / stream_read_gbs, 4),
+        "decoder_block": {"layers": LAYERS, "us_four_launches": round(event_ms_per_step * 1e3, 2),
+                          "us_one_grouped_launch": round(group_us, 2),
+                          "us_one_grouped_launch_p10_p90": [round(float(np.percentile(group_ms, 10)) * 1e3, 2),
+                                                            round(float(np.percentile(group_ms, 90)) * 1e3, 2)],
+                          "grouped_gbs": round(total_bytes / (group_us * 1e-6) / 1e9, 1),
+                          "grouped_frac_of_8TBs": round(total_bytes / (group_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                          "grouped_outputs_equal_separate_launches_bitwise": group_equal,
+                          "note": "lutgemm_gemv_group: one launch for four independent products; `value` is NOT "
+                                  "this figure but the four separate launches a dependent chain needs"},
         "per_layer": per_layer,
         "fc1_batch_sweep": batch_sweep,
         "paper_context": {"fc1_ms": PAPER_A100_FC1_MS, "hardware": "A100-80GB (paper table 1)"},

@@ -191,6 +191,32 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
                  int q, int g, int mu, int64_t m, int64_t n, unsigned flags,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* DEVICE pointers in host arrays.  `count` (1..8) independent products y[i] = What_i x[i] in
+   ONE kernel launch, e.g. the four linear layers of a decoder block (appendix A: attention
+   QKV and output projections, the two feed-forward layers) when their inputs are at hand,
+   the separate Q / K / V or gate / up projections of one activation vector, or the experts
+   of a mixture layer.  Arguments as lutgemm_gemv, per layer:
+     x[i], bits[i], alpha[i], y[i]   device pointers of layer i, shape m[i] x n[i];
+     z                               NULL (no layer has offsets) or an array of `count`
+                                     offset buffers
+   and q, g, mu, flags common to all layers (with g == 0 every layer's group size is its own
+   n; the group sizes must then fall in the same class: all multiples of 64, or of 32, or of
+   16, else LUTGEMM_EUNSUPPORTED, as are group sizes that are not multiples of 16).  Workspace of lutgemm_group_workspace_bytes(m, n, count, q,
+   g, mu) bytes, prepared like any other (lutgemm_workspace_init once).
+   Every layer runs on the grid it would have alone; the workgroups of layer i + 1 follow those
+   of layer i onto the compute units as these become free, so the end of one product (its
+   stragglers, its cross-tile sums) and the start of the next (activation fetch, table build)
+   overlap with streaming instead of leaving the memory system half idle: on the OPT-175B
+   layers the four products take less time than four launches.  The layers must not depend
+   on one another: a layer's x must not be another layer's y.  For dependent layers, call
+   lutgemm_gemv once per layer on one stream; they may share one workspace.
+   Each y[i] is bit for bit what lutgemm_gemv gives for that layer.                      */
+int lutgemm_gemv_group(const void* const* x, const void* const* bits, const void* const* alpha,
+                       const void* const* z, void* const* y, const int64_t* m, const int64_t* n, int count,
+                       int q, int g, int mu, unsigned flags, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+size_t lutgemm_group_workspace_bytes(const int64_t* m, const int64_t* n, int count, int q, int g, int mu);
+
 /* For callers that cannot allocate device memory or pass a workspace along: code that runs
    under HIP graph capture, tight serving loops, harnesses that forbid allocation.
    lutgemm_gemv with the same arguments minus the workspace: the scratch memory is an array

@@ -1,7 +1,6 @@
 """Build liblutgemm.so (gfx950) in-tree with hipcc.  `python -m paper_2206_09557_amd.build`.
 
-The device source is compiled once per kernel family (-DLUT_PART=k: ten translation units of
-the one file csrc/lutgemm_device.hip) in parallel, then linked with the host source."""
+The device source is compiled once per kernel family (-DLUT_PART=k) in parallel, then linked with the host source."""
 from __future__ import annotations
 
 import os
@@ -15,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "liblutgemm.so")
 HOST_SOURCE = os.path.join(PKG, "csrc", "lutgemm_host.cpp")
 DEVICE_SOURCE = os.path.join(PKG, "csrc", "lutgemm_device.hip")
-PARTS = 10   # kernel families of lutgemm_device.hip (LUT_PART = 0 .. 9)
+PARTS = 13   # kernel families of lutgemm_device.hip (LUT_PART = 0 .. 12)
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-pthread",

@@ -71,10 +71,9 @@ struct GemvParams {
   int batch;
 };
 
-// Row range of this workgroup in row units: ranges differ by at most one unit.  (Grid x =
-// K group, grid y = row range: no division anywhere in the kernel preamble.)
-__device__ __forceinline__ void row_range(const GemvParams& p, int* u0, int* u1) {
-  const int rs = blockIdx.y;
+// Row range rs in row units: ranges differ by at most one unit.  (Grid x = K group, grid y =
+// row range: no division anywhere in the preamble of the one-layer kernels.)
+__device__ __forceinline__ void row_range(const GemvParams& p, int rs, int* u0, int* u1) {
   *u0 = rs * p.range_base + min(rs, p.range_rem);
   *u1 = *u0 + p.range_base + (rs < p.range_rem ? 1 : 0);
 }
@@ -644,16 +643,14 @@ __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut
     __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// One workgroup of a GEMV: K group kg, row range rs of layer p.  The lookup addresses are formed
+// as if `lut` started at LDS address 0: it is the only LDS object of the kernels that call
+// this, which the host verifies before the first launch of each of them (lds_layout_ok).
 // AM2 / AM1: scale modes of the two-sub-slab tiles and of a one-sub-slab last tile.
 template <int Q, bool HAS_Z, int AM2, int AM1>
-__global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
-  __shared__ float lut[kGemvLdsFloats];
-  // The lookup addresses are formed as if the tables start at LDS address 0.
-  if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
-  const int kg = blockIdx.x;
-  const int rs = blockIdx.y;
+__device__ __forceinline__ void gemv_workgroup(const GemvParams& p, float* lut, int kg, int rs) {
   int rb0, rb1;
-  row_range(p, &rb0, &rb1);
+  row_range(p, rs, &rb0, &rb1);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
   const bool direct = p.NT == 1;   // one tile, hence one K group: the sums of the tile are y
   const int kt_end = min((kg + 1) * p.TPG, p.NT);
@@ -679,6 +676,38 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
 
   if (carry) flush_row_sums(p, lut, rb0, rb1, partial);
   if (!direct) finish_row_range<1>(p, lut, rs, rb0, rb1);
+}
+
+template <int Q, bool HAS_Z, int AM2, int AM1>
+__global__ __launch_bounds__(kThreads) void lutgemm_gemv_kernel(GemvParams p) {
+  __shared__ float lut[kGemvLdsFloats];
+  gemv_workgroup<Q, HAS_Z, AM2, AM1>(p, lut, blockIdx.x, blockIdx.y);
+}
+
+// Several independent GEMVs in one launch (lutgemm_gemv_group): a one-dimensional grid, the
+// workgroups of layer 0 first, then those of layer 1, and so on, each layer with the grid it
+// would have on its own.  Workgroups are handed to compute units in that order as earlier
+// ones leave, so the last workgroups of a layer (stragglers, the last-arrival sums) share the
+// device with the first of the next (activation fetch, table build, first weights): the
+// start and the end of a launch, which a GEMV alone spends with the memory system half
+// idle, overlap with streaming.
+constexpr int kMaxGroup = 8;
+struct GroupParams {
+  GemvParams layer[kMaxGroup];
+  int first_wg[kMaxGroup + 1];   // first_wg[i] .. first_wg[i + 1] - 1: workgroups of layer i
+  int count;
+};
+
+template <int Q, bool HAS_Z, int AM2, int AM1>
+__global__ __launch_bounds__(kThreads) void lutgemm_gemv_group_kernel(GroupParams gp) {
+  __shared__ float lut[kGemvLdsFloats];
+  int li = 0;
+  for (int k = 1; k < gp.count; ++k)
+    if ((int)blockIdx.x >= gp.first_wg[k]) li = k;
+  const GemvParams& p = gp.layer[li];
+  const int local = (int)blockIdx.x - gp.first_wg[li];
+  const int rs = local / p.KG;
+  gemv_workgroup<Q, HAS_Z, AM2, AM1>(p, lut, local - rs * p.KG, rs);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -801,7 +830,9 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
   const u32x4 xraw0 = *reinterpret_cast<const u32x4*>(xp);
   const u32x4 xraw1 = *reinterpret_cast<const u32x4*>(xp + p.n);
 
-  constexpr int PP = Q > 4 ? (Q + 1) / 2 : Q;
+  // planes fetched together: all up to four; beyond that half of them, or three where every
+  // dword has a scale set of its own (a set is 2 * planes registers per dword)
+  constexpr int PP = Q > 4 ? ((AMODE & 3) == kAlphaQuad ? (Q + 1) / 2 : 3) : Q;
   // Units fetched ahead (D): as many as the registers of a wavefront hold, up to kDepth.  A
   // unit is the key words plus a scale set (and offsets) per dword when the scales are not
   // shared by the quad.  A unit is only 1 KB per plane, so it takes two of them in flight
@@ -933,12 +964,11 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
 
 template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
-  __shared__ float lut[kLutBytes / 4 + 4];
-  if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
+  __shared__ float lut[kLutBytes / 4 + 4];   // (the kernel's only LDS object: see gemv_workgroup)
   const int kg = blockIdx.x;
   const int rs = blockIdx.y;
   int rb0, rb1;
-  row_range(p, &rb0, &rb1);
+  row_range(p, rs, &rb0, &rb1);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
   for (int ti = 0; ti < p.TPG; ++ti) {
     const int h = kg * p.TPG + ti;
@@ -990,6 +1020,9 @@ const void* quad_family0(int q, int64_t g);
 const void* quad_family1(int q, int64_t g);
 const void* quad_family2(int q, int64_t g);
 const void* planes_family(int q, bool has_z, int batch);
+const void* group_family0(int q, int64_t g);
+const void* group_family1(int q, int64_t g);
+const void* group_family2(int q, int64_t g);
 }  // namespace lutgemm_parts
 
 namespace {
@@ -1021,6 +1054,34 @@ GemvKernel pick_mode(int q, int64_t g) {
 GemvKernel pick_kernel(int q, bool has_z, bool shared, int64_t g) {
   if (shared) return lutgemm_parts::gemv_family2(q, g);
   return has_z ? lutgemm_parts::gemv_family1(q, g) : lutgemm_parts::gemv_family0(q, g);
+}
+
+template <bool HAS_Z, int AM2, int AM1>
+GemvKernel pick_group_q(int q) {
+  switch (q) {
+    case 1: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<1, HAS_Z, AM2, AM1>);
+    case 2: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<2, HAS_Z, AM2, AM1>);
+    case 3: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<3, HAS_Z, AM2, AM1>);
+    case 4: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<4, HAS_Z, AM2, AM1>);
+    case 5: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<5, HAS_Z, AM2, AM1>);
+    case 6: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<6, HAS_Z, AM2, AM1>);
+    case 7: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<7, HAS_Z, AM2, AM1>);
+    case 8: return reinterpret_cast<const void*>(lutgemm_gemv_group_kernel<8, HAS_Z, AM2, AM1>);
+  }
+  return nullptr;
+}
+
+template <bool HAS_Z, int SH>
+GemvKernel pick_group_mode(int q, int64_t g) {   // as pick_mode, without the register-bound scale set per chunk
+  if (g % 64 == 0) return pick_group_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
+  if (g % 32 == 0) return pick_group_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
+  if (g % 16 == 0) return pick_group_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
+  return nullptr;
+}
+
+GemvKernel pick_group_kernel(int q, bool has_z, bool shared, int64_t g) {
+  if (shared) return lutgemm_parts::group_family2(q, g);
+  return has_z ? lutgemm_parts::group_family1(q, g) : lutgemm_parts::group_family0(q, g);
 }
 
 // Pair kernel: a lane's dword is one chunk, so the per-chunk scale mode does not occur.
@@ -1314,6 +1375,15 @@ const void* quad_family1(int q, int64_t g) { return pick_quad_mode<true, 0>(q, g
 #if LUT_HAS_PART(8)
 const void* quad_family2(int q, int64_t g) { return pick_quad_mode<true, kAlphaShared>(q, g); }
 #endif
+#if LUT_HAS_PART(10)
+const void* group_family0(int q, int64_t g) { return pick_group_mode<false, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(11)
+const void* group_family1(int q, int64_t g) { return pick_group_mode<true, 0>(q, g); }
+#endif
+#if LUT_HAS_PART(12)
+const void* group_family2(int q, int64_t g) { return pick_group_mode<true, kAlphaShared>(q, g); }
+#endif
 #if LUT_HAS_PART(9)
 const void* planes_family(int q, bool has_z, int batch) {
   if (batch <= 16) return has_z ? pick_planes_q<true, 1>(q) : pick_planes_q<false, 1>(q);
@@ -1352,6 +1422,39 @@ __global__ __launch_bounds__(kProbeThreads) void lutgemm_stream_read_kernel(cons
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) w ^= (uint32_t)__shfl_xor((int)w, d, 64);
   if ((threadIdx.x & 63) == 0) sink[blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6)] = w;
+}
+
+// The lookup kernels form LDS addresses as if their table array started at LDS address 0, which
+// holds when that array is the kernel's only LDS object.  Verified on the host before the first
+// launch of every kernel: its static LDS size must be exactly the array's (anything else in
+// LDS would make it larger), else the call fails with LUTGEMM_EHIP instead of computing
+// nonsense.
+bool lds_layout_ok(const void* kernel, size_t table_array_bytes) {
+  static std::mutex lock;
+  static const void* verified[1024];
+  static int n_verified = 0;
+  std::lock_guard<std::mutex> guard(lock);
+  for (int i = 0; i < n_verified; ++i)
+    if (verified[i] == kernel) return true;
+  hipFuncAttributes attr;
+  if (hipFuncGetAttributes(&attr, kernel) != hipSuccess) return false;
+  if (attr.sharedSizeBytes != table_array_bytes) return false;
+  if (n_verified < 1024) verified[n_verified++] = kernel;
+  return true;
+}
+
+// Shape-derived fields of a launch.
+void fill_shape(GemvParams* p, int64_t m, int64_t n, int64_t gg) {
+  p->m = (int)m;
+  p->n = (int)n;
+  p->RB = (int)((m + 15) / 16);
+  p->nchunks = (int)(n / 8);
+  p->NT = (p->nchunks + 127) / 128;
+  p->NG = (int)(n / gg);
+  p->g = (int)gg;
+  p->g_shift = -1;
+  for (int sh = 0; sh < 31; ++sh)
+    if ((gg >> 3) == ((int64_t)1 << sh)) p->g_shift = sh;
 }
 
 extern "C" {
@@ -1400,15 +1503,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   p.bits = static_cast<const uint8_t*>(bits);
   p.alpha = static_cast<const __half*>(alpha);
   p.z = static_cast<const __half*>(z);
-  p.m = (int)m;
-  p.RB = (int)((m + 15) / 16);
-  p.nchunks = (int)(n / 8);
-  p.NT = (p.nchunks + 127) / 128;
-  p.NG = (int)(n / gg);
-  p.g = (int)gg;
-  p.g_shift = -1;
-  for (int sh = 0; sh < 31; ++sh)
-    if ((gg >> 3) == ((int64_t)1 << sh)) p.g_shift = sh;
+  fill_shape(&p, m, n, gg);
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
   plan_grid(cus, 1, q, gg, &p);
   const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;   // an even number of row blocks (the quad kernel works on pairs)
@@ -1422,7 +1517,6 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   uint32_t* counters = static_cast<uint32_t*>(workspace);
   p.spare = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
-  p.n = (int)n;
   p.vec_stride = m_pad;
   const size_t y_elem = p.y_f32 ? sizeof(float) : sizeof(__half);
 
@@ -1459,6 +1553,8 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     pb.range_base = row_units / pb.row_splits;
     pb.range_rem = row_units % pb.row_splits;
     void* args[] = {&pb};
+    if (!lds_layout_ok(kb, (take == 1 ? (size_t)kGemvLdsFloats : (size_t)(kLutBytes / 4 + 4)) * sizeof(float)))
+      return LUTGEMM_EHIP;
     if (hipLaunchKernel(kb, dim3(pb.KG, pb.row_splits), dim3(kThreads), args, 0,
                         stream) != hipSuccess)
       return LUTGEMM_EHIP;
@@ -1491,17 +1587,8 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   p.alpha = static_cast<const __half*>(alpha);
   p.z = static_cast<const __half*>(z);
   p.y = y;
-  p.m = (int)m;
-  p.n = (int)n;
+  fill_shape(&p, m, n, gg);
   p.batch = batch;
-  p.RB = (int)((m + 15) / 16);
-  p.nchunks = (int)(n / 8);
-  p.NT = (p.nchunks + 127) / 128;
-  p.NG = (int)(n / gg);
-  p.g = (int)gg;
-  p.g_shift = -1;
-  for (int sh = 0; sh < 31; ++sh)
-    if ((gg >> 3) == ((int64_t)1 << sh)) p.g_shift = sh;
   p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
   const int waves = q > 4 ? 4 : 8;
   plan_planes_grid(cus, waves, batch, &p);
@@ -1578,6 +1665,92 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
                  int q, int g, int mu, int64_t m, int64_t n, unsigned flags,
                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   return lutgemm_gemm(x, bits, alpha, z, y, q, g, mu, m, n, 1, flags, workspace, workspace_bytes, hip_stream);
+}
+
+size_t lutgemm_group_workspace_bytes(const int64_t* m, const int64_t* n, int count, int q, int g, int mu) {
+  if (!m || !n || count < 1 || count > kMaxGroup) return 0;
+  size_t total = kCounterBytes + kSpareBytes;
+  for (int i = 0; i < count; ++i) {
+    const size_t one = lutgemm_workspace_bytes(m[i], n[i], q, g, mu, 1);
+    if (one == 0) return 0;
+    total += (one - kCounterBytes - kSpareBytes + 255) / 256 * 256;   // the layer's partial sums
+  }
+  return total;
+}
+
+int lutgemm_gemv_group(const void* const* x, const void* const* bits, const void* const* alpha, const void* const* z,
+                       void* const* y, const int64_t* m, const int64_t* n, int count, int q, int g, int mu,
+                       unsigned flags, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!x || !bits || !alpha || !y || !m || !n || !workspace || !aligned16(workspace)) return LUTGEMM_EINVAL;
+  if (count < 1 || q < 1 || q > 8 || g < 0) return LUTGEMM_EINVAL;
+  if (mu != 8 || count > kMaxGroup || (flags & ~3u) != 0) return LUTGEMM_EUNSUPPORTED;
+  const bool shared = (flags & LUTGEMM_ALPHA_SHARED) != 0;
+  if (shared && !z) return LUTGEMM_EINVAL;
+  const int cus = compute_units_of_device();
+  if (cus <= 0) return LUTGEMM_EHIP;
+
+  GroupParams gp;
+  gp.count = count;
+  gp.first_wg[0] = 0;
+  uint32_t* counters = static_cast<uint32_t*>(workspace);
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
+  size_t used = kCounterBytes + kSpareBytes;
+  int64_t g_first = -1;
+  for (int i = 0; i < count; ++i) {
+    if (!x[i] || !bits[i] || !alpha[i] || !y[i] || (z && !z[i])) return LUTGEMM_EINVAL;
+    if (m[i] < 1 || n[i] < 8 || n[i] % 8 != 0) return LUTGEMM_EINVAL;
+    if (m[i] > (int64_t)1 << 30 || n[i] > (int64_t)1 << 30) return LUTGEMM_EUNSUPPORTED;
+    const int64_t gg = g == 0 ? n[i] : g;
+    if (gg % 8 != 0 || n[i] % gg != 0) return LUTGEMM_EINVAL;
+    // one kernel serves the group, and the kernel is chosen by how the group size divides a
+    // quad's 64 columns: row-wise scales (g == 0) must put every layer in the same class
+    const int64_t cls = gg % 64 == 0 ? 64 : (gg % 32 == 0 ? 32 : (gg % 16 == 0 ? 16 : 8));
+    if (g_first < 0) g_first = cls;
+    if (cls != g_first) return LUTGEMM_EUNSUPPORTED;
+    if (!aligned16(x[i]) || !aligned16(bits[i]) || !aligned16(alpha[i]) || !aligned16(y[i]) || (z && !aligned16(z[i])))
+      return LUTGEMM_EINVAL;
+    GemvParams& p = gp.layer[i];
+    p = GemvParams();
+    p.x = static_cast<const __half*>(x[i]);
+    p.bits = static_cast<const uint8_t*>(bits[i]);
+    p.alpha = static_cast<const __half*>(alpha[i]);
+    p.z = z ? static_cast<const __half*>(z[i]) : nullptr;
+    p.y = y[i];
+    fill_shape(&p, m[i], n[i], gg);
+    p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
+    p.batch = 1;
+    plan_grid(cus, 1, q, gg, &p);
+    if (p.TPG > 1 && carries_in_lds(q, gg) && (p.RB + p.row_splits - 1) / p.row_splits > kRunBlocks)
+      return LUTGEMM_EUNSUPPORTED;   // (never planned)
+    if (p.row_splits > 256) return LUTGEMM_EUNSUPPORTED;   // 256 arrival counters per layer
+    const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;
+    p.kg_stride = m_pad;
+    p.vec_stride = m_pad;
+    p.range_base = p.RB / p.row_splits;
+    p.range_rem = p.RB % p.row_splits;
+    p.counters = counters + (size_t)i * 256;
+    p.partial = partials;
+    p.spare = nullptr;
+    const size_t one = lutgemm_workspace_bytes(m[i], n[i], q, g, mu, 1);
+    if (one == 0) return LUTGEMM_EINVAL;
+    const size_t part_bytes = (one - kCounterBytes - kSpareBytes + 255) / 256 * 256;
+    partials += part_bytes / sizeof(float);
+    used += part_bytes;
+    const int64_t wgs = (int64_t)p.KG * p.row_splits;
+    if (gp.first_wg[i] + wgs > (int64_t)1 << 30) return LUTGEMM_EUNSUPPORTED;
+    gp.first_wg[i + 1] = gp.first_wg[i] + (int)wgs;
+  }
+  for (int i = count; i < kMaxGroup; ++i) gp.first_wg[i + 1] = gp.first_wg[count];
+  if (workspace_bytes < used) return LUTGEMM_EWORKSPACE;
+  const int64_t gg0 = g == 0 ? n[0] : g;
+  GemvKernel kern = pick_group_kernel(q, z != nullptr, shared, gg0);
+  if (!kern) return LUTGEMM_EUNSUPPORTED;
+  if (!lds_layout_ok(kern, (size_t)kGemvLdsFloats * sizeof(float))) return LUTGEMM_EHIP;
+  void* args[] = {&gp};
+  if (hipLaunchKernel(kern, dim3(gp.first_wg[count]), dim3(kThreads), args, 0, static_cast<hipStream_t>(hip_stream)) !=
+      hipSuccess)
+    return LUTGEMM_EHIP;
+  return LUTGEMM_OK;
 }
 
 // ---------------------------------------------------------------------------------------

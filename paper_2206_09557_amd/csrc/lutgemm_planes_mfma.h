@@ -349,7 +349,7 @@ __global__ __launch_bounds__(PlanesCfg<Q>::kThreadsM) void lutgemm_planes_mfma_k
   const int kg = blockIdx.x;
   const int rs = blockIdx.y;
   int rb0, rb1;
-  row_range(p, &rb0, &rb1);
+  row_range(p, rs, &rb0, &rb1);
   const int kt0 = kg * p.TPG;
   const int kt1 = min(kt0 + p.TPG, p.NT);
 

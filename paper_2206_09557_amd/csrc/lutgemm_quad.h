@@ -248,12 +248,11 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
 // half does not exist in a ragged last tile are skipped.  Row ranges start at even row blocks.
 template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_quad_kernel(GemvParams p) {
-  __shared__ float lut[kLutBytes / 4 + 4];
-  if ((uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut != 0u) return;
+  __shared__ float lut[kLutBytes / 4 + 4];   // (the kernel's only LDS object: see gemv_workgroup)
   const int kg = blockIdx.x;
   const int rs = blockIdx.y;
   int pair0, pair1;                 // row units are pairs of row blocks here
-  row_range(p, &pair0, &pair1);
+  row_range(p, rs, &pair0, &pair1);
   const int rb0 = 2 * pair0;
   const int rb1 = min(2 * pair1, p.RB);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;

@@ -34,6 +34,10 @@ _SIGNATURES = {
     "lutgemm_gemv": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                 _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_uint,
                                 _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "lutgemm_gemv_group": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                      _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_uint,
+                                      _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "lutgemm_group_workspace_bytes": (_c.c_size_t, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int]),
     "lutgemm_gemv_static": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                        _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_uint, _c.c_void_p]),
     "lutgemm_static_scratch_bytes": (_c.c_size_t, []),
@@ -198,6 +202,28 @@ def lutgemm_workspace_init(workspace, workspace_bytes, stream=0):
 def lutgemm_gemv(x, bits, alpha, z, y, q, g, mu, m, n, flags, workspace, workspace_bytes, stream=0):
     _check(lib().lutgemm_gemv(_addr(x), _addr(bits), _addr(alpha), _addr(z), _addr(y), q, g, mu, m, n, flags,
                               _addr(workspace), workspace_bytes, stream or None), "lutgemm_gemv")
+
+
+def _pointer_array(objs):
+    return (ctypes.c_void_p * len(objs))(*[_addr(o) for o in objs])
+
+
+def _int64_array(values):
+    return (ctypes.c_int64 * len(values))(*[int(v) for v in values])
+
+
+def lutgemm_group_workspace_bytes(m, n, q, g, mu=8):
+    """m, n: sequences of the layers' shapes."""
+    return lib().lutgemm_group_workspace_bytes(_int64_array(m), _int64_array(n), len(m), q, g, mu)
+
+
+def lutgemm_gemv_group(x, bits, alpha, z, y, m, n, q, g, mu, flags, workspace, workspace_bytes, stream=0):
+    """x, bits, alpha, y (and z, or None): sequences of device buffers, one per layer."""
+    count = len(m)
+    zs = None if z is None else _pointer_array(z)
+    _check(lib().lutgemm_gemv_group(_pointer_array(x), _pointer_array(bits), _pointer_array(alpha), zs,
+                                    _pointer_array(y), _int64_array(m), _int64_array(n), count, q, g, mu, flags,
+                                    _addr(workspace), workspace_bytes, stream or None), "lutgemm_gemv_group")
 
 
 def lutgemm_gemv_static(x, bits, alpha, z, y, q, g, mu, m, n, flags, stream=0):
