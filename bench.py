@@ -277,8 +277,9 @@ def main():
                           "grid": {"k_groups": kg, "tiles_per_k_group": tpg, "row_ranges": rs}})
 
     # ---- small batch on the FC1 shape (section 6 of the paper), outside the timed regions:
-    # the lookup path (lutgemm_gemm), the matrix-core path (lutgemm_gemm_mfma) and
-    # lutgemm_gemm left to choose between them, side by side ----
+    # the lookup path (lutgemm_gemm), the plane-wise matrix-core path (lutgemm_gemm_mfma), the
+    # dequantise-to-fp16-then-multiply comparison kernel (lutgemm_gemm_dequant_mfma) and
+    # lutgemm_gemm left to choose between the first two, side by side ----
     fc1 = layers[2]
     batch_sweep = []
     for bsz in (() if args.no_batch_sweep else (1, 2, 4, 8, 16, 32)):
@@ -304,10 +305,11 @@ def main():
 
         us = timed(L.lutgemm_gemm, L.LUTGEMM_Y_F16)
         us_mfma = timed(L.lutgemm_gemm_mfma, L.LUTGEMM_Y_F16)
+        us_dequant = timed(L.lutgemm_gemm_dequant_mfma, L.LUTGEMM_Y_F16)
         us_auto = timed(L.lutgemm_gemm, L.LUTGEMM_Y_F16 | L.LUTGEMM_PATH_AUTO)
         batch_sweep.append({"batch": bsz, "lut_us": round(us, 2), "lut_us_per_vector": round(us / bsz, 2),
                             "mfma_us": round(us_mfma, 2), "mfma_us_per_vector": round(us_mfma / bsz, 2),
-                            "auto_us": round(us_auto, 2)})
+                            "dequant_mfma_us": round(us_dequant, 2), "auto_us": round(us_auto, 2)})
         del xb, yb, wsg
 
     us_regions = [w * 1e3 / nL for w in wall_ms]

@@ -259,6 +259,21 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
                       int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Same arguments as lutgemm_gemm_mfma; the comparison kernel of the small-batch workload:
+   dequantise, then multiply on the matrix cores (the dequantisation-based kind of kernel the
+   paper sets its method against in section 2.2 and section 4).  Every 8 weights of a row are
+   rebuilt as fp16 values  What = sum_i alpha_i b_i + z  (eq. 3) in packed fp16 arithmetic and
+   ONE matrix-core instruction per 32 columns multiplies them with the activations (fp32
+   accumulation).  The fp16 rounding of What is part of the method: y agrees with the exact
+   product to a relative L2 error of about 3e-4 (bound asked of it: 1e-3), not to the 1e-5
+   of the other paths' fp32 outputs.  Same restrictions as lutgemm_gemm_mfma.  Bitwise
+   reproducible.  Measured beside the plane-wise form on MI355X (49152 x 12288, q = 3): 157 us
+   against 124 us up to 16 activation vectors, 185 against 183 at 32: rebuilding fp16
+   weights buys nothing over multiplying the planes, and costs accuracy.                  */
+int lutgemm_gemm_dequant_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                              int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* HOST.  The workgroup grid the lookup kernels are launched with for an m x n layer of q
    planes and group size g, as chosen from these alone (appendix B: every block owns a tile
    of the weights and a set of tables; the partial outputs of the blocks along a row are

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "liblutgemm.so")
 HOST_SOURCE = os.path.join(PKG, "csrc", "lutgemm_host.cpp")
 DEVICE_SOURCE = os.path.join(PKG, "csrc", "lutgemm_device.hip")
-PARTS = 13   # kernel families of lutgemm_device.hip (LUT_PART = 0 .. 12)
+PARTS = 14   # kernel families of lutgemm_device.hip (LUT_PART = 0 .. 13)
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-pthread",

@@ -1020,6 +1020,7 @@ const void* quad_family0(int q, int64_t g);
 const void* quad_family1(int q, int64_t g);
 const void* quad_family2(int q, int64_t g);
 const void* planes_family(int q, bool has_z, int batch);
+const void* dequant_family(int q, bool has_z, int batch);
 const void* group_family0(int q, int64_t g);
 const void* group_family1(int q, int64_t g);
 const void* group_family2(int q, int64_t g);
@@ -1299,6 +1300,21 @@ constexpr size_t kSpareBytes = 256 * 16 * 32 * sizeof(float);   // 128 bytes per
 
 
 template <bool HAS_Z, int NB>
+GemvKernel pick_dequant_q(int q) {
+  switch (q) {
+    case 1: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<1, HAS_Z, NB, true>);
+    case 2: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<2, HAS_Z, NB, true>);
+    case 3: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<3, HAS_Z, NB, true>);
+    case 4: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<4, HAS_Z, NB, true>);
+    case 5: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<5, HAS_Z, NB, true>);
+    case 6: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<6, HAS_Z, NB, true>);
+    case 7: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<7, HAS_Z, NB, true>);
+    case 8: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<8, HAS_Z, NB, true>);
+  }
+  return nullptr;
+}
+
+template <bool HAS_Z, int NB>
 GemvKernel pick_planes_q(int q) {
   switch (q) {
     case 1: return reinterpret_cast<const void*>(lutgemm_planes_mfma_kernel<1, HAS_Z, NB>);
@@ -1383,6 +1399,12 @@ const void* group_family1(int q, int64_t g) { return pick_group_mode<true, 0>(q,
 #endif
 #if LUT_HAS_PART(12)
 const void* group_family2(int q, int64_t g) { return pick_group_mode<true, kAlphaShared>(q, g); }
+#endif
+#if LUT_HAS_PART(13)
+const void* dequant_family(int q, bool has_z, int batch) {
+  if (batch <= 16) return has_z ? pick_dequant_q<true, 1>(q) : pick_dequant_q<false, 1>(q);
+  return has_z ? pick_dequant_q<true, 2>(q) : pick_dequant_q<false, 2>(q);
+}
 #endif
 #if LUT_HAS_PART(9)
 const void* planes_family(int q, bool has_z, int batch) {
@@ -1563,9 +1585,9 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   return LUTGEMM_OK;
 }
 
-int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
-                      int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
-                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int gemm_matrix_cores(bool dequant, const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                             int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!x || !bits || !alpha || !y || !workspace) return LUTGEMM_EINVAL;
   if (m < 1 || n < 8 || n % 8 != 0 || q < 1 || q > 8 || g < 0 || batch < 1) return LUTGEMM_EINVAL;
   const int64_t gg = g == 0 ? n : g;
@@ -1610,7 +1632,7 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
   p.counters = static_cast<uint32_t*>(workspace);
   p.spare = nullptr;
   p.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
-  GemvKernel kern = pick_planes_kernel(q, z != nullptr, batch);
+  GemvKernel kern = dequant ? lutgemm_parts::dequant_family(q, z != nullptr, batch) : pick_planes_kernel(q, z != nullptr, batch);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
   if (p.row_splits > 65535) return LUTGEMM_EUNSUPPORTED;   // grid y
   p.range_base = p.RB / p.row_splits;
@@ -1620,6 +1642,18 @@ int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const 
                       static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return LUTGEMM_EHIP;
   return LUTGEMM_OK;
+}
+
+int lutgemm_gemm_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                      int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return gemm_matrix_cores(false, x, bits, alpha, z, y, q, g, mu, m, n, batch, flags, workspace, workspace_bytes, hip_stream);
+}
+
+int lutgemm_gemm_dequant_mfma(const void* x, const void* bits, const void* alpha, const void* z, void* y,
+                              int q, int g, int mu, int64_t m, int64_t n, int batch, unsigned flags,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return gemm_matrix_cores(true, x, bits, alpha, z, y, q, g, mu, m, n, batch, flags, workspace, workspace_bytes, hip_stream);
 }
 
 int lutgemm_plan_grid(int64_t m, int64_t n, int q, int g, int vectors, int compute_units, int* out) {

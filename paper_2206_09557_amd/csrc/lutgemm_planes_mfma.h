@@ -146,6 +146,76 @@ __device__ __forceinline__ void planes_issue(PlanesOperands<Q, NB, T>& o, const 
   }
 }
 
+// The dequantising variant of planes_compute (DQ): the comparison kernel the small-batch
+// workload names and the kind of kernel the paper's section 2.2 / section 4 discuss as
+// dequantisation-based.  The +-1 operands of the planes are combined, in packed fp16
+// arithmetic, into the fp16 weights  What = sum_i alpha_i b_i + z  of the lane's operand row
+// (eq. 3), and ONE matrix-core instruction per 32 columns multiplies them with the
+// activations, accumulating straight into the outputs.  The fp16 rounding of What costs about
+// 3e-4 relative error in y, which the plane-wise form does not have.
+template <int Q, bool HAS_Z, int NB, int T>
+__device__ __forceinline__ void dequant_compute(const GemvParams& p, const PlanesTile& t, int lane, const u32x2* sign,
+                                                const f16x8* Xs, const uint32_t* stage, const unsigned char* astage,
+                                                const unsigned char* zstage, f32x4 (&fin)[NB]) {
+  constexpr int NB16 = NB * 16;
+  const int sub = lane >> 4;        // slot within the block
+  const int col = lane & 15;        // row supplied to the A operand / activation vector of the outputs
+  const int key_shift = 8 * (col & 3);
+  const uint32_t* my_stage = stage + 4 * (col >> 2) + ((sub - (col >> 2)) & 3);
+  const u32x2* my_sign = sign + (lane & 31);
+  const f16x8* my_x = Xs + (T * sub) * NB16 + col;
+  // scales and offset of the lane's OPERAND row (row `col` of the block) in group segment seg:
+  // staging layout [segment][quarter of 4 rows][plane][4 rows] fp16, offsets [segment][16 rows]
+  const unsigned char* my_alpha = astage + (col >> 2) * Q * 8 + (col & 3) * 2;
+  const unsigned char* my_z = zstage + col * 2;
+  f16x8 a8[Q], z8;
+  auto load_scales = [&](int seg) {
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+      const _Float16 h = *reinterpret_cast<const _Float16*>(my_alpha + (seg * 4 * Q + i) * 8);
+      a8[i] = f16x8{h, h, h, h, h, h, h, h};
+    }
+    const _Float16 zh = HAS_Z ? *reinterpret_cast<const _Float16*>(my_z + seg * 32) : (_Float16)0.0f;
+    z8 = f16x8{zh, zh, zh, zh, zh, zh, zh, zh};
+  };
+  int seg = 0;
+  const int seg_blocks = p.g / (32 * T);
+  int left = (p.g - (1024 * t.kt) % p.g) / (32 * T);   // blocks until the first group ends
+  load_scales(0);
+#pragma unroll 1
+  for (int j0 = 0; j0 < t.nblk; j0 += 4) {
+    uint32_t kd[Q][T][4];
+#pragma unroll
+    for (int i = 0; i < Q; ++i)
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) kd[i][tt][jj] = my_stage[i * 512 + (tt * 16 + j0 + jj) * 16];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + jj;
+      PlanesOperands<Q, NB, T> o;
+      planes_issue<Q, NB, T>(o, kd, jj, j, key_shift, my_sign, my_x);
+      if (j < t.nblk) {   // wave-uniform
+#pragma unroll
+        for (int tt = 0; tt < T; ++tt) {
+          f16x8 w = z8;   // eq. 3 for eight columns of the operand row, rounded to fp16 at every step
+#pragma unroll
+          for (int i = 0; i < Q; ++i) w = o.a[tt][i] * a8[i] + w;
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) fin[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(w, o.b[tt][nb], fin[nb], 0, 0, 0);
+        }
+        --left;
+        if (left == 0 && j != t.nblk - 1) {   // wave-uniform: the next block starts a new group
+          left = seg_blocks;
+          seg = min(seg + 1, t.nseg - 1);
+          load_scales(seg);
+        }
+      }
+    }
+  }
+}
+
 template <int Q, bool HAS_Z, int NB, int T>
 __device__ __forceinline__ void planes_compute(const GemvParams& p, const PlanesTile& t, int lane, const u32x2* sign,
                                                const float* blksum, const f16x8* Xs, const uint32_t* stage,
@@ -319,7 +389,7 @@ __device__ __forceinline__ void finish_rows_batch(const GemvParams& p, uint32_t*
   if (threadIdx.x == 0) __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int Q, bool HAS_Z, int NB>
+template <int Q, bool HAS_Z, int NB, bool DQ = false>
 __global__ __launch_bounds__(PlanesCfg<Q>::kThreadsM) void lutgemm_planes_mfma_kernel(GemvParams p) {
   using C = PlanesCfg<Q>;
   constexpr int NB16 = NB * 16;
@@ -397,7 +467,7 @@ __global__ __launch_bounds__(PlanesCfg<Q>::kThreadsM) void lutgemm_planes_mfma_k
     }
     __syncthreads();
     if (kAheadX) fetch_x_tile(min(kt + 1, kt1 - 1));
-    if (HAS_Z) {   // sum of the activations of every block (the offset term needs it per group)
+    if (HAS_Z && !DQ) {   // sum of the activations of every block (the offset term needs it per group)
       for (int idx = threadIdx.x; idx < 16 * NB16; idx += kThr) {
         const int j = idx / NB16, n = idx % NB16;
         float s = 0.0f;
@@ -423,12 +493,20 @@ __global__ __launch_bounds__(PlanesCfg<Q>::kThreadsM) void lutgemm_planes_mfma_k
           const PlanesTile tn = planes_tile_info(p, kt + 1, Q);
           planes_fetch(raw, p, tn, rb0 + wave, lane);
         }
-        if (t.T == 2)
+        if constexpr (DQ) {
+          if (t.T == 2)
+            dequant_compute<Q, HAS_Z, NB, 2>(p, t, lane, sign, reinterpret_cast<const f16x8*>(Xs), stage, astage, zstage,
+                                             fin[u]);
+          else
+            dequant_compute<Q, HAS_Z, NB, 1>(p, t, lane, sign, reinterpret_cast<const f16x8*>(Xs), stage, astage, zstage,
+                                             fin[u]);
+        } else if (t.T == 2) {
           planes_compute<Q, HAS_Z, NB, 2>(p, t, lane, sign, blksum, reinterpret_cast<const f16x8*>(Xs), stage, astage,
                                           zstage, fin[u]);
-        else
+        } else {
           planes_compute<Q, HAS_Z, NB, 1>(p, t, lane, sign, blksum, reinterpret_cast<const f16x8*>(Xs), stage, astage,
                                           zstage, fin[u]);
+        }
       }
     }
   }

@@ -47,6 +47,9 @@ _SIGNATURES = {
     "lutgemm_gemm_mfma": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                      _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_int, _c.c_uint,
                                      _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "lutgemm_gemm_dequant_mfma": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                             _c.c_int, _c.c_int, _c.c_int, _c.c_int64, _c.c_int64, _c.c_int, _c.c_uint,
+                                             _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "lutgemm_plan_grid": (_c.c_int, [_c.c_int64, _c.c_int64, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p]),
     "lutgemm_stream_read": (_c.c_int, [_c.c_void_p, _c.c_size_t, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "lutgemm_strerror": (_c.c_char_p, [_c.c_int]),
@@ -247,3 +250,9 @@ def lutgemm_stream_read(src, nbytes, sink, sink_bytes, stream=0):
 def lutgemm_gemm_mfma(x, bits, alpha, z, y, q, g, mu, m, n, batch, flags, workspace, workspace_bytes, stream=0):
     _check(lib().lutgemm_gemm_mfma(_addr(x), _addr(bits), _addr(alpha), _addr(z), _addr(y), q, g, mu, m, n, batch,
                                    flags, _addr(workspace), workspace_bytes, stream or None), "lutgemm_gemm_mfma")
+
+
+def lutgemm_gemm_dequant_mfma(x, bits, alpha, z, y, q, g, mu, m, n, batch, flags, workspace, workspace_bytes, stream=0):
+    _check(lib().lutgemm_gemm_dequant_mfma(_addr(x), _addr(bits), _addr(alpha), _addr(z), _addr(y), q, g, mu, m, n,
+                                           batch, flags, _addr(workspace), workspace_bytes, stream or None),
+           "lutgemm_gemm_dequant_mfma")

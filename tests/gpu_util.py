@@ -48,7 +48,7 @@ def make_workspace(nbytes, stream=None):
     return d_ws
 
 
-def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, shared=False, auto=False):
+def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, shared=False, auto=False, dequant=False):
     """y (numpy) of lutgemm_gemv (1-D x) or lutgemm_gemm (2-D x; lutgemm_gemm_mfma if mfma) for the packed layer.
     y is pre-filled with NaN: it must be fully overwritten, never read."""
     torch = torch_cuda()
@@ -70,10 +70,13 @@ def run(packed, x16, f32_out=False, stream=None, workspace=None, mfma=False, sha
     if auto:     # lutgemm_gemm picks the path
         flags |= L.LUTGEMM_PATH_AUTO
     torch.cuda.synchronize()
-    if mfma:
+    if dequant:   # the dequantise-then-multiply comparison kernel
+        L.lutgemm_gemm_dequant_mfma(d_x, p.d_bits, d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
+                                    d_ws.numel(), s.cuda_stream)
+    elif mfma:
         L.lutgemm_gemm_mfma(d_x, p.d_bits, d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, batch, flags, d_ws,
                             d_ws.numel(), s.cuda_stream)
-    elif x16.ndim == 1:
+    elif x16.ndim == 1 and not dequant:
         L.lutgemm_gemv(d_x, p.d_bits, d_alpha, p.d_z, d_y, p.q, p.g, 8, p.m, p.n, flags, d_ws, d_ws.numel(),
                        s.cuda_stream)
     else:
@@ -105,12 +108,15 @@ def row_l1_bound(alpha, z, g_cols):
     return RowBounds(g_cols * s.sum(axis=1), s.max(axis=1))
 
 
-def check_parity(y_gpu, y_ref, x16, rowbound, f32_out=False):
+def check_parity(y_gpu, y_ref, x16, rowbound, f32_out=False, fp16_weights=False):
     """Tolerances of the workload statement: relative L2 <= 1e-3 and max abs <=
     1e-2 * |x|_inf * sum(alpha), the sum read per row as a bound on the row's L1 norm.
     fp32 output is held to relative L2 <= 1e-5 and, element by element, to the literal
     reading |y - y_ref| <= 1e-2 * |x|_inf * max_G sum_i alpha[i][r][G] (about 1e-3 on the
-    benchmark layers, far below any row's magnitude: a lost or stale partial sum fails it)."""
+    benchmark layers, far below any row's magnitude: a lost or stale partial sum fails it).
+    fp16_weights: the output of the dequantising comparison kernel, whose method rounds every
+    rebuilt weight to fp16: held to the fp16-output tolerances whatever its output type."""
+    f32_out = f32_out and not fp16_weights
     y_gpu = np.asarray(y_gpu, dtype=np.float64)
     assert np.all(np.isfinite(y_gpu))
     rel = np.linalg.norm(y_gpu - y_ref) / max(np.linalg.norm(y_ref), 1e-30)

@@ -147,6 +147,20 @@ def test_mfma_path_on_fc1_shape(batch):
         check_parity(Y[b], Yref[b], X[b], bound, f32_out=True)
 
 
+@pytest.mark.parametrize("batch", [1, 8])
+def test_dequant_mfma_kernel_on_fc1_shape(batch):
+    # the comparison kernel of the small-batch workload at the size it is timed on, every row
+    m, n = synth.OPT_175B["fc1"]
+    q, g = 3, 128
+    print(f"case dequant fc1 m={m} n={n} batch={batch}", flush=True)
+    p, bound = _fc1_packed()
+    X = synth.activations_fp16(n, seed=5800 + batch, batch=batch)
+    Y = run(p, X, f32_out=True, dequant=True)
+    Yref, _ = c_oracle.gemv_packed(p.bits, p.alpha, None, X, m, n, q, g)
+    for b in range(batch):
+        check_parity(Y[b], Yref[b], X[b], bound, f32_out=True, fp16_weights=True)
+
+
 def test_mfma_path_llama65b_down_with_offset():
     m, n = synth.LLAMA_65B["down"]
     q, g = 4, 128

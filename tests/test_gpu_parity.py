@@ -185,6 +185,28 @@ def test_mfma_path_matches_oracle(m, n, q, g, mode, batch):
     np.testing.assert_array_equal(run(p, X, f32_out=True, mfma=True), Y32)   # bitwise reproducible
 
 
+@pytest.mark.parametrize("m,n,q,g,mode,batch", MFMA_CASES)
+def test_dequant_mfma_kernel_matches_oracle_to_fp16_weight_rounding(m, n, q, g, mode, batch):
+    # the dequantise-then-multiply comparison kernel: same oracle; its method rounds the rebuilt
+    # weights to fp16, so it is held to relative L2 <= 1e-3 and the row-L1 bound, not to 1e-5
+    print(f"case dequant m={m} n={n} q={q} g={g} mode={mode} batch={batch}", flush=True)
+    W = synth.weights_fp16(m, n, seed=6000 + m + 7 * n + q)
+    X = synth.activations_fp16(n, seed=6500 + m + n, batch=batch)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    bound = _bound(p)
+    Y32 = run(p, X, f32_out=True, dequant=True)
+    assert Y32.shape == (batch, m)
+    worst = 0.0
+    for b in range(batch):
+        worst = max(worst, check_parity(Y32[b], _oracle_full(p, X[b]), X[b], bound, f32_out=True, fp16_weights=True))
+    print(f"worst relative L2 {worst:.2e}", flush=True)
+    np.testing.assert_array_equal(Y32.astype(np.float16), run(p, X, dequant=True))
+    np.testing.assert_array_equal(run(p, X, f32_out=True, dequant=True), Y32)   # bitwise reproducible
+    # and it is a different computation from the plane-wise path, not an alias of it
+    if q > 1:
+        assert not np.array_equal(Y32, run(p, X, f32_out=True, mfma=True))
+
+
 def test_mfma_path_rejects_groups_not_multiple_of_64():
     m, n, q, g = 64, 1024, 2, 32
     W = synth.weights_fp16(m, n, seed=6900)
