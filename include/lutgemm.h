@@ -153,7 +153,9 @@ int lutgemm_workspace_init(void* workspace, size_t workspace_bytes, void* hip_st
 int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int mu, int mode,
                      void* bits_out, uint16_t* alpha_out, uint16_t* z_out);
 
-/* HOST.  Decode packed bits back to B_pm1[q][m][n] in {-1,+1} (int8, host memory).      */
+/* HOST.  Decode packed bits back to the binary planes B_pm1[q][m][n] in {-1,+1} (int8, host
+   memory): the b_i of section 2.3's  w ~ sum_i alpha_i b_i, bit j of the key of chunk c being
+   column 8c + j (section 3.1's keys read back).  Inverse of lutgemm_pack_planes.       */
 int lutgemm_unpack_bcq(const void* bits, int64_t m, int64_t n, int q, int mu, int8_t* B_pm1);
 
 /* HOST.  Write already-known planes B_pm1[q][m][n] (entries -1/+1) in the packed bits

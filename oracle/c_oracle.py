@@ -13,7 +13,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle_gemv.c")
-_LIB = os.path.join(_HERE, "liboracle_gemv.so")
+_LIB = os.environ.get("ORACLE_GEMV_LIB") or os.path.join(_HERE, "liboracle_gemv.so")   # (override: sanitizer build)
 _lib = None
 
 

@@ -51,41 +51,40 @@ def main(argv=None):
         cases = [("", args.m, args.n, q, g, args.layout) for q in [int(v) for v in args.q.split(",")]
                  for g in [int(v) for v in args.g.split(",")]]
     for name, m, n, q, g, layout in cases:
-        if True:
-            x = torch.randn(n, device="cuda", generator=gen).half()
-            y = torch.empty(m, dtype=torch.float16, device="cuda")
-            args.layout = layout
-            nb = L.lutgemm_bits_bytes(m, n, q)
-            na = L.lutgemm_alpha_shared_bytes(m, n, g) if args.layout == "shared" else L.lutgemm_alpha_bytes(m, n, q, g)
-            nz = 0 if args.layout == "planes" else L.lutgemm_z_bytes(m, n, g)
-            copies = max(2, min(80, -(-int(1.0e9) // (nb + na + nz))))   # about 1 GB in rotation: nothing stays cached
-            bits = [torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=gen) for _ in range(copies)]
-            alpha = [(torch.rand(na // 2, device="cuda", generator=gen) * 0.05 + 0.001).half() for _ in range(copies)]
-            zs = [None] * copies if nz == 0 else [(torch.rand(nz // 2, device="cuda", generator=gen) * 0.02 - 0.01).half()
-                                                  for _ in range(copies)]
-            flags = L.LUTGEMM_Y_F16 | (L.LUTGEMM_ALPHA_SHARED if args.layout == "shared" else 0)
-            wsb = L.lutgemm_workspace_bytes(m, n, q, g)
-            ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
-            L.lutgemm_workspace_init(ws, wsb, stream)
+        x = torch.randn(n, device="cuda", generator=gen).half()
+        y = torch.empty(m, dtype=torch.float16, device="cuda")
+        args.layout = layout
+        nb = L.lutgemm_bits_bytes(m, n, q)
+        na = L.lutgemm_alpha_shared_bytes(m, n, g) if args.layout == "shared" else L.lutgemm_alpha_bytes(m, n, q, g)
+        nz = 0 if args.layout == "planes" else L.lutgemm_z_bytes(m, n, g)
+        copies = max(2, min(80, -(-int(1.0e9) // (nb + na + nz))))   # about 1 GB in rotation: nothing stays cached
+        bits = [torch.randint(0, 256, (nb,), dtype=torch.uint8, device="cuda", generator=gen) for _ in range(copies)]
+        alpha = [(torch.rand(na // 2, device="cuda", generator=gen) * 0.05 + 0.001).half() for _ in range(copies)]
+        zs = [None] * copies if nz == 0 else [(torch.rand(nz // 2, device="cuda", generator=gen) * 0.02 - 0.01).half()
+                                              for _ in range(copies)]
+        flags = L.LUTGEMM_Y_F16 | (L.LUTGEMM_ALPHA_SHARED if args.layout == "shared" else 0)
+        wsb = L.lutgemm_workspace_bytes(m, n, q, g)
+        ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+        L.lutgemm_workspace_init(ws, wsb, stream)
 
-            def go(i):
-                L.lutgemm_gemv(x, bits[i % copies], alpha[i % copies], zs[i % copies], y, q, g, 8, m, n, flags, ws, wsb,
-                               stream)
+        def go(i):
+            L.lutgemm_gemv(x, bits[i % copies], alpha[i % copies], zs[i % copies], y, q, g, 8, m, n, flags, ws, wsb,
+                           stream)
 
-            for i in range(5):
-                go(i)
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for i in range(args.iters):
-                go(i)
-            b.record()
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / args.iters
-            gg = n if g == 0 else g
-            footprint = m * n * q // 8 + na + nz                    # bits + scales (+ offsets), bytes
-            rows.append((name, m, n, layout, q, g, footprint, us))
-            del bits, alpha, zs, ws
-            print(f"[sweep] {name} {m}x{n} q={q} g={g or 'row'}: {us:.2f} us", file=sys.stderr, flush=True)
+        for i in range(5):
+            go(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(args.iters):
+            go(i)
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / args.iters
+        gg = n if g == 0 else g
+        footprint = m * n * q // 8 + na + nz                    # bits + scales (+ offsets), bytes
+        rows.append((name, m, n, layout, q, g, footprint, us))
+        del bits, alpha, zs, ws
+        print(f"[sweep] {name} {m}x{n} q={q} g={g or 'row'}: {us:.2f} us", file=sys.stderr, flush=True)
     if args.preset == "workloads":
         print("| layer | m x n | q | g | offsets | footprint MB | us / GEMV | GB/s | % of 8 TB/s |")
         print("|---|---|---|---|---|---|---|---|---|")
