@@ -223,8 +223,8 @@ def main():
     # where every layer has weights of its own) ----
     def time_alone(ent, rotate, regions=9, reps=20):
         us = []
-        for _ in range(3):
-            launch(ent, 0)
+        for s in range(60):     # (the copies between the passes leave the device idle for a moment)
+            launch(ent, s if rotate else 0)
         for r in range(regions):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()

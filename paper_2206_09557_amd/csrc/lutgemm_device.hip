@@ -1182,15 +1182,25 @@ const Tuning& tuning() {
   return t;
 }
 
-// Workgroup grid: KG groups of TPG consecutive K tiles times row_splits row ranges, one
-// workgroup per compute unit.  Cost model in units of one (tile, row block) per wavefront:
-// the slowest wavefront's units plus a table build per tile, plus the cross-group sum.
 // How the GEMV kernel of a (q, g) layer carries row sums from tile to tile of a K group: the
 // variants that fetch a unit in one piece keep them in LDS, which bounds the row range of a
 // workgroup; the register-bound ones (more than four planes, or a scale set per chunk:
 // g % 16 != 0) send them through the workspace.
 bool carries_in_lds(int q, int64_t g) { return q <= 4 && g % 16 == 0; }
 
+// Workgroup grid: KG groups of TPG consecutive K tiles times row_splits row ranges, one
+// workgroup per compute unit.  Cost model in units of one round of units of a workgroup (16
+// units, one per wavefront: about 4 us when the whole device streams), fitted to twelve layer
+// shapes (OPT-13B, OPT-175B, LLaMA-65B) timed with weights that no cache holds:
+//   * per tile, the rounds of units of a row range (the queue lets the wavefronts share a
+//     partly filled round once there are several; one or two rounds cost whole rounds) plus
+//     0.6 rounds for the activations, the table build and the first fetch;
+//   * per K group, the partial sums it writes and the last-arrival sum reads back, which grow
+//     with the rows (0.13 rounds per group at 49152 rows), and a small charge per workgroup
+//     column.
+// With the running sums of a K group in LDS, two tiles per group beat one on the tall layers
+// with 12 tiles (36864 and 49152 rows x 12288: 6 groups instead of 12), three beat one on
+// 12288 x 49152; the small layers keep one tile per group.
 void choose_grid(int cus, int NT, int RB, bool lds_carry, int* KG, int* TPG, int* RS) {
   double best = 1e30;
   const int max_rs = (RB + kWaves - 1) / kWaves;
@@ -1199,10 +1209,11 @@ void choose_grid(int cus, int NT, int RB, bool lds_carry, int* KG, int* TPG, int
     int rs = cus / kg;
     rs = rs < 1 ? 1 : (rs > max_rs ? max_rs : rs);
     const int blocks = (RB + rs - 1) / rs;
-    const int rounds = (blocks + kWaves - 1) / kWaves;
+    const double rounds = blocks >= 3 * kWaves ? (double)blocks / kWaves : (double)((blocks + kWaves - 1) / kWaves);
     const int tiles = (NT + kg - 1) / kg;
     if (lds_carry && tpg > 1 && blocks > kRunBlocks) continue;   // the running sums of a row range live in LDS
-    const double cost = tiles * (rounds + 0.5) + 0.03 * kg + 0.3 * (tpg - 1);
+    // (the variants that carry sums through memory pay a round trip per tile on top)
+    const double cost = tiles * (rounds + 0.6) + 0.03 * kg + 0.13 * kg * (RB / 3072.0) + (lds_carry ? 0.0 : 0.3 * (tpg - 1));
     if (cost < best) {
       best = cost;
       *KG = kg;
