@@ -593,9 +593,17 @@ __device__ __forceinline__ void reduce_rows(const GemvParams& p, int rb0, int ro
   }
 }
 
-template <int NVEC, int RPP>
+// FINE: also batches of 4, 6 and 8 groups (the kernels with registers and code space for them:
+// on the tall OPT-175B layers, which run 6 K groups, a batch of 12 wastes half its loads).
+template <int NVEC, int RPP, bool FINE>
 __device__ __forceinline__ void reduce_rows_by_groups(const GemvParams& p, int rb0, int row_end) {
-  if (p.KG <= 12)
+  if (FINE && p.KG <= 4)
+    reduce_rows<NVEC, RPP, 4>(p, rb0, row_end);
+  else if (FINE && p.KG <= 6)
+    reduce_rows<NVEC, RPP, 6>(p, rb0, row_end);
+  else if (FINE && p.KG <= 8)
+    reduce_rows<NVEC, RPP, 8>(p, rb0, row_end);
+  else if (p.KG <= 12)
     reduce_rows<NVEC, RPP, 12>(p, rb0, row_end);
   else
     reduce_rows<NVEC, RPP, 16>(p, rb0, row_end);
@@ -604,7 +612,7 @@ __device__ __forceinline__ void reduce_rows_by_groups(const GemvParams& p, int r
 // Cross-group reduction by the last workgroup to arrive for a row range, for NVEC activation
 // vectors (appendix B accumulates the per-block partial outputs with atomics; here the
 // groups are added in index order by whoever arrives last, so y is reproducible bit for bit).
-template <int NVEC>
+template <int NVEC, bool FINE = false>
 __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut, int rs, int rb0, int rb1) {
   // Hand-off of the partials to whichever workgroup arrives last for this row range, ordered
   // by completion rather than by fences:
@@ -634,11 +642,11 @@ __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut
   const int row_end = min(rb1 * 16, p.m);
   const int rows = row_end - rb0 * 16;
   if (rows <= kThreads)
-    reduce_rows_by_groups<NVEC, 1>(p, rb0, row_end);
+    reduce_rows_by_groups<NVEC, 1, FINE>(p, rb0, row_end);
   else if (rows <= 2 * kThreads)
-    reduce_rows_by_groups<NVEC, 2>(p, rb0, row_end);
+    reduce_rows_by_groups<NVEC, 2, FINE>(p, rb0, row_end);
   else
-    reduce_rows_by_groups<NVEC, 3>(p, rb0, row_end);
+    reduce_rows_by_groups<NVEC, 3, FINE>(p, rb0, row_end);
   if (threadIdx.x == 0)            // leave the counter at zero for the next call on this workspace
     __hip_atomic_store(p.counters + rs, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -675,7 +683,7 @@ __device__ __forceinline__ void gemv_workgroup(const GemvParams& p, float* lut, 
   }
 
   if (carry) flush_row_sums(p, lut, rb0, rb1, partial);
-  if (!direct) finish_row_range<1>(p, lut, rs, rb0, rb1);
+  if (!direct) finish_row_range<1, (Q <= 4)>(p, lut, rs, rb0, rb1);
 }
 
 template <int Q, bool HAS_Z, int AM2, int AM1>
