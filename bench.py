@@ -184,6 +184,30 @@ def main():
     avg_launch_bytes = total_bytes / nL
     achieved = avg_launch_bytes / (avg_launch_us * 1e-6) / 1e9
 
+    # ---- per-layer breakdown, outside the timed regions: each shape alone, back to back,
+    # rotating through its copies; then the same with ONE weight copy (whatever the last-level
+    # cache keeps of it stays there between launches: "hot", not a figure a decoder sees,
+    # where every layer has weights of its own) ----
+    def time_alone(ent, rotate, regions=9, reps=20):
+        us = []
+        for s in range(60):     # (the copies between the passes leave the device idle for a moment)
+            launch(ent, s if rotate else 0)
+        for r in range(regions):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record(stream)
+            for s in range(reps):
+                launch(ent, (r * reps + s) if rotate else 0)
+            b.record(stream)
+            torch.cuda.synchronize()
+            us.append(a.elapsed_time(b) * 1e3 / reps)
+        return us
+
+    alone = [time_alone(ent, True) for ent in layers]
+    for li, ent in enumerate(layers):      # a second round in the same order: 18 regions per layer
+        alone[li] += time_alone(ent, True)
+    hot = [time_alone(ent, False) for ent in layers]
+
     # ---- the same step as ONE grouped launch (lutgemm_gemv_group): the four products are
     # independent here (each has its own input), so the workgroups of one layer may follow
     # those of the previous one onto the device without a kernel boundary in between ----
@@ -216,30 +240,6 @@ def main():
         group_ms.append(ev0.elapsed_time(ev1) / args.steps)
     group_equal = all(bool(torch.equal(a, e["y"])) for a, e in zip(yg, layers))
     group_us = float(np.median(group_ms)) * 1e3
-
-    # ---- per-layer breakdown, outside the timed regions: each shape alone, back to back,
-    # rotating through its copies; then the same with ONE weight copy (whatever the last-level
-    # cache keeps of it stays there between launches: "hot", not a figure a decoder sees,
-    # where every layer has weights of its own) ----
-    def time_alone(ent, rotate, regions=9, reps=20):
-        us = []
-        for s in range(60):     # (the copies between the passes leave the device idle for a moment)
-            launch(ent, s if rotate else 0)
-        for r in range(regions):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            a.record(stream)
-            for s in range(reps):
-                launch(ent, (r * reps + s) if rotate else 0)
-            b.record(stream)
-            torch.cuda.synchronize()
-            us.append(a.elapsed_time(b) * 1e3 / reps)
-        return us
-
-    alone = [time_alone(ent, True) for ent in layers]
-    for li, ent in enumerate(layers):      # a second round in the same order: 18 regions per layer
-        alone[li] += time_alone(ent, True)
-    hot = [time_alone(ent, False) for ent in layers]
 
     # fp32 output of every layer, once, for the parity report
     y32 = []
