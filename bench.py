@@ -48,7 +48,7 @@ PAPER_A100_FC1_MS = 0.2250
 # step), measured offline with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each
 # scaled by what the counter reads for a 256 MiB copy kernel in the same run: summary in
 # profiles/lutgemm_gemv_kernel_opt175b_q3_g128_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = 195.0e6
+MEASURED_TRAFFIC_BYTES = 193.3e6
 
 
 def algorithmic_bytes(m, n, q, g, batch=1, with_z=False):
