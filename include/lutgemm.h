@@ -133,9 +133,9 @@ size_t lutgemm_z_bytes(int64_t m, int64_t n, int g);
    ((r / 16) * NG + G) * 16 + r % 16, the layout of z.                                   */
 size_t lutgemm_alpha_shared_bytes(int64_t m, int64_t n, int g);
 
-/* Device scratch a gemv/gemm call needs: 32 KB of arrival counters, 512 KB that take
-   results nobody reads, and the split-K partial sums (the per-block partial outputs that
-   appendix B accumulates across thread blocks).  0 on invalid arguments.                */
+/* Device scratch a gemv/gemm call needs: 32 KB of arrival counters and the split-K partial
+   sums (the per-block partial outputs that appendix B accumulates across thread blocks).
+   0 on invalid arguments.                                                               */
 size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch);
 
 /* DEVICE.  Enqueue the one-time preparation of a freshly allocated workspace (zeroes its

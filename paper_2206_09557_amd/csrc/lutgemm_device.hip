@@ -66,7 +66,6 @@ struct GemvParams {
   // pair kernel only
   int n;                  // columns
   int64_t vec_stride;     // floats between the partials of the two vectors of a pair
-  float* spare;           // [256 workgroup slots][16 wavefronts][2][16]: where results nobody reads are stored
   // matrix-core kernel: activation vectors; quad kernel: live vectors of this launch (3 or 4)
   int batch;
 };
@@ -550,44 +549,88 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
 // Addresses are clamped, not predicated, so RPP and KB are chosen to fit the row range and
 // the group count (a clamped load is a wasted load); the sum over the groups of a row always
 // runs in ascending group order.
-template <int NVEC, int RPP, int KB>
+template <int RPP, int KB>
 __device__ __forceinline__ void reduce_rows(const GemvParams& p, int rb0, int row_end) {
+  for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += RPP * kThreads) {
+    const float* src[RPP];
+    float sum[RPP];
 #pragma unroll
-  for (int vec = 0; vec < NVEC; ++vec) {
-    if (NVEC == 4 && vec >= p.batch) continue;   // a quad launched for three vectors: nothing to write for the fourth
-    const float* part = NVEC == 1 ? p.partial : p.partial + (int64_t)vec * p.vec_stride;
-    for (int r0 = rb0 * 16 + (int)threadIdx.x; r0 < row_end; r0 += RPP * kThreads) {
-      const float* src[RPP];
-      float sum[RPP];
+    for (int j = 0; j < RPP; ++j) {
+      src[j] = p.partial + min(r0 + j * kThreads, row_end - 1);
+      sum[j] = 0.0f;
+    }
+    for (int kb = 0; kb < p.KG; kb += KB) {
+      float v[RPP][KB];
 #pragma unroll
-      for (int j = 0; j < RPP; ++j) {
-        src[j] = part + min(r0 + j * kThreads, row_end - 1);
-        sum[j] = 0.0f;
-      }
-      for (int kb = 0; kb < p.KG; kb += KB) {
-        float v[RPP][KB];
+      for (int u = 0; u < KB; ++u) {
+        const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
 #pragma unroll
-        for (int u = 0; u < KB; ++u) {
-          const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
-#pragma unroll
-          for (int j = 0; j < RPP; ++j) v[j][u] = load_device_coherent(src[j] + off);
-        }
-#pragma unroll
-        for (int u = 0; u < KB; ++u) {
-          const bool live = kb + u < p.KG;
-#pragma unroll
-          for (int j = 0; j < RPP; ++j) sum[j] += live ? v[j][u] : 0.0f;
-        }
+        for (int j = 0; j < RPP; ++j) v[j][u] = load_device_coherent(src[j] + off);
       }
 #pragma unroll
-      for (int j = 0; j < RPP; ++j) {
-        const int r = r0 + j * kThreads;
-        if (r < row_end) {
-          if (p.y_f32)
-            static_cast<float*>(p.y)[(int64_t)vec * p.m + r] = sum[j];
-          else   // fp16 output, nearest even (paper table 1)
-            static_cast<__half*>(p.y)[(int64_t)vec * p.m + r] = __float2half_rn(sum[j]);
-        }
+      for (int u = 0; u < KB; ++u) {
+        const bool live = kb + u < p.KG;
+#pragma unroll
+        for (int j = 0; j < RPP; ++j) sum[j] += live ? v[j][u] : 0.0f;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < RPP; ++j) {
+      const int r = r0 + j * kThreads;
+      if (r < row_end) {
+        if (p.y_f32)
+          static_cast<float*>(p.y)[r] = sum[j];
+        else   // fp16 output, nearest even (paper table 1)
+          static_cast<__half*>(p.y)[r] = __float2half_rn(sum[j]);
+      }
+    }
+  }
+}
+
+// The same for NVEC activation vectors (2 or 4; a quad launched for three vectors has nothing
+// to write for the fourth).  The (vector, row) pairs of the range are dealt to the threads as
+// ONE list, RPP of them per thread per pass, so that the passes of the workgroup, each a
+// round trip to memory, are as few as the rows allow.
+template <int NVEC, int RPP, int KB>
+__device__ __forceinline__ void reduce_vector_rows(const GemvParams& p, int rb0, int row_end) {
+  const int row0 = rb0 * 16;
+  const int rows = row_end - row0;
+  const int items = (NVEC == 4 ? min(p.batch, 4) : NVEC) * rows;
+  for (int i0 = (int)threadIdx.x; i0 < items; i0 += RPP * kThreads) {
+    const float* src[RPP];
+    float sum[RPP];
+#pragma unroll
+    for (int j = 0; j < RPP; ++j) {
+      const int i = min(i0 + j * kThreads, items - 1);
+      const int vec = i / rows;
+      src[j] = p.partial + (int64_t)vec * p.vec_stride + (row0 + i - vec * rows);
+      sum[j] = 0.0f;
+    }
+    for (int kb = 0; kb < p.KG; kb += KB) {
+      float v[RPP][KB];
+#pragma unroll
+      for (int u = 0; u < KB; ++u) {
+        const int64_t off = (int64_t)min(kb + u, p.KG - 1) * p.kg_stride;
+#pragma unroll
+        for (int j = 0; j < RPP; ++j) v[j][u] = load_device_coherent(src[j] + off);
+      }
+#pragma unroll
+      for (int u = 0; u < KB; ++u) {
+        const bool live = kb + u < p.KG;
+#pragma unroll
+        for (int j = 0; j < RPP; ++j) sum[j] += live ? v[j][u] : 0.0f;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < RPP; ++j) {
+      const int i = i0 + j * kThreads;
+      if (i < items) {
+        const int vec = i / rows;
+        const int64_t dst = (int64_t)vec * p.m + (row0 + i - vec * rows);
+        if (p.y_f32)
+          static_cast<float*>(p.y)[dst] = sum[j];
+        else
+          static_cast<__half*>(p.y)[dst] = __float2half_rn(sum[j]);
       }
     }
   }
@@ -595,18 +638,26 @@ __device__ __forceinline__ void reduce_rows(const GemvParams& p, int rb0, int ro
 
 // FINE: also batches of 4, 6 and 8 groups (the kernels with registers and code space for them:
 // on the tall OPT-175B layers, which run 6 K groups, a batch of 12 wastes half its loads).
+template <int NVEC, int RPP, int KB>
+__device__ __forceinline__ void reduce_rows_batched(const GemvParams& p, int rb0, int row_end) {
+  if constexpr (NVEC == 1)
+    reduce_rows<RPP, KB>(p, rb0, row_end);
+  else
+    reduce_vector_rows<NVEC, RPP, KB>(p, rb0, row_end);
+}
+
 template <int NVEC, int RPP, bool FINE>
 __device__ __forceinline__ void reduce_rows_by_groups(const GemvParams& p, int rb0, int row_end) {
   if (FINE && p.KG <= 4)
-    reduce_rows<NVEC, RPP, 4>(p, rb0, row_end);
+    reduce_rows_batched<NVEC, RPP, 4>(p, rb0, row_end);
   else if (FINE && p.KG <= 6)
-    reduce_rows<NVEC, RPP, 6>(p, rb0, row_end);
+    reduce_rows_batched<NVEC, RPP, 6>(p, rb0, row_end);
   else if (FINE && p.KG <= 8)
-    reduce_rows<NVEC, RPP, 8>(p, rb0, row_end);
+    reduce_rows_batched<NVEC, RPP, 8>(p, rb0, row_end);
   else if (p.KG <= 12)
-    reduce_rows<NVEC, RPP, 12>(p, rb0, row_end);
+    reduce_rows_batched<NVEC, RPP, 12>(p, rb0, row_end);
   else
-    reduce_rows<NVEC, RPP, 16>(p, rb0, row_end);
+    reduce_rows_batched<NVEC, RPP, 16>(p, rb0, row_end);
 }
 
 // Cross-group reduction by the last workgroup to arrive for a row range, for NVEC activation
@@ -640,7 +691,7 @@ __device__ __forceinline__ void finish_row_range(const GemvParams& p, float* lut
   __syncthreads();
   if (flag[0] == 0u) return;
   const int row_end = min(rb1 * 16, p.m);
-  const int rows = row_end - rb0 * 16;
+  const int rows = NVEC * (row_end - rb0 * 16);   // (vector, row) pairs to sum
   if (rows <= kThreads)
     reduce_rows_by_groups<NVEC, 1, FINE>(p, rb0, row_end);
   else if (rows <= 2 * kThreads)
@@ -759,30 +810,49 @@ __device__ __forceinline__ void table_entries16(int kh, int hi, const float (&xs
   }
 }
 
+// The lookups of one (plane, row-of-four) step: the four dwords' key bytes, one 8-byte read each.
+template <int Q, int I0, int QP, int AMODE, bool HAS_Z>
+__device__ __forceinline__ void pair_lookups(const Unit<Q, I0, QP, 1, AMODE, HAS_Z>& u, const uint32_t (&lane_base)[4],
+                                             int step, f32x2 (&e)[4]) {
+  const int i = step >> 2, rho = step & 3;
+  // address bytes {0, L / 32, key byte rho, (L % 32) * 8}: lane_base holds bytes 0 and 2 (as its bytes 0 and 1)
+  const uint32_t sel = 0x0c010000u | ((4u + rho) << 8);
+#pragma unroll
+  for (int s = 0; s < 4; ++s) e[s] = lds_f32x2(__builtin_amdgcn_perm(u.w[i][0][s], lane_base[s], sel));
+}
+
+// Software-pipelined by hand: the reads of step k + 1 are in flight while the additions of
+// step k run (the scheduling barriers keep it so; left to itself the compiler waits for
+// every read or two right after issuing them).
 template <int Q, int I0, int QP, int AMODE, bool HAS_Z>
 __device__ __forceinline__ void accumulate_pair(const Unit<Q, I0, QP, 1, AMODE, HAS_Z>& u, const uint32_t (&lane_base)[4],
                                                 const f32x2 (&sum_x)[4], float (&acc)[2][4]) {
   using U = Unit<Q, I0, QP, 1, AMODE, HAS_Z>;
+  constexpr int kSteps = 4 * QP;
+  // (with a scale set per dword the registers hold one step's reads only)
+  constexpr int kAhead = (AMODE & 3) == kAlphaQuad ? 1 : 0;
+  f32x2 e[kAhead + 1][4];
+  if (kAhead) pair_lookups(u, lane_base, 0, e[0]);
 #pragma unroll
-  for (int i = 0; i < QP; ++i) {
-#pragma unroll
-    for (int rho = 0; rho < 4; ++rho) {
-      // address bytes {0, L / 32, key byte rho, (L % 32) * 8}: lane_base holds bytes 0 and 2 (as its bytes 0 and 1)
-      const uint32_t sel = 0x0c010000u | ((4u + rho) << 8);
-      float run0 = 0.0f, run1 = 0.0f;
+  for (int step = 0; step < kSteps; ++step) {
+    if (step + kAhead < kSteps) pair_lookups(u, lane_base, step + kAhead, e[(step + kAhead) & kAhead]);
+    __builtin_amdgcn_sched_barrier(0);
+    const int i = step >> 2, rho = step & 3;
+    const f32x2(&cur)[4] = e[step & kAhead];
+    if ((AMODE & 3) == kAlphaQuad) {   // section 3.2 rule 2: one scale per run of lookups
+      const f32x2 run = (cur[0] + cur[1]) + (cur[2] + cur[3]);
+      const float a = scale_of<AMODE>(u.al[0][0], i, I0 + i, rho);
+      acc[0][rho] = fmaf(a, run.x, acc[0][rho]);
+      acc[1][rho] = fmaf(a, run.y, acc[1][rho]);
+    } else {
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const f32x2 e = lds_f32x2(__builtin_amdgcn_perm(u.w[i][0][s], lane_base[s], sel));
-        const bool first = ((AMODE & 3) == kAlphaQuad) ? (s == 0) : true;
-        run0 = first ? e.x : run0 + e.x;
-        run1 = first ? e.y : run1 + e.y;
-        if ((AMODE & 3) != kAlphaQuad || s == 3) {   // section 3.2 rule 2: one scale per run of lookups
-          const float a = scale_of<AMODE>(u.al[((AMODE & 3) == kAlphaQuad) ? 0 : s][0], i, I0 + i, rho);
-          acc[0][rho] = fmaf(a, run0, acc[0][rho]);
-          acc[1][rho] = fmaf(a, run1, acc[1][rho]);
-        }
+        const float a = scale_of<AMODE>(u.al[s][0], i, I0 + i, rho);
+        acc[0][rho] = fmaf(a, cur[s].x, acc[0][rho]);
+        acc[1][rho] = fmaf(a, cur[s].y, acc[1][rho]);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
   }
   if (HAS_Z && I0 == 0) {   // offset term of eq. 3
 #pragma unroll
@@ -811,10 +881,21 @@ __device__ __forceinline__ void pair_passes(const GemvParams& p, int64_t tile_ba
     pair_passes<Q, I0 + QP, PP, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, tile_T, t0, lane_base, sum_x, acc);
 }
 
+// The activations lane L needs for the table build of half tile h (sub-slab h % 2 of K
+// tile h / 2): the 8 halfs of its slot's chunk, of vector v.
+__device__ __forceinline__ u32x4 pair_fetch_x(const GemvParams& p, int h, int v, int lane) {
+  const int kt = h >> 1, t0 = h & 1;
+  const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
+  const int tile_T = chunks_in_tile > 64 ? 2 : 1;
+  const int chunk = min(tile_T * lane + t0, chunks_in_tile - 1);   // clamped: value unused if out of range
+  return *reinterpret_cast<const u32x4*>(p.x + (int64_t)(128 * kt + chunk) * 8 + (int64_t)v * p.n);
+}
+
 // One workgroup, one half tile (kt, t0), row blocks [rb0, rb1).  kDepth as in tile_body.
+// xraw0, xraw1: what pair_fetch_x returned for this half tile and the two vectors.
 template <int Q, int AMODE, bool HAS_Z, int kDepth>
 __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, int kt, int t0, int rb0, int rb1,
-                                               float* partial, bool first_tile) {
+                                               bool first_tile, const u32x4& xraw0, const u32x4& xraw1) {
   using U = Unit<Q, 0, Q, 1, AMODE, HAS_Z>;
   int lane = threadIdx.x & 63;
   asm volatile("" : "+v"(lane));   // see tile_body
@@ -823,8 +904,6 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
   const int tile_T = chunks_in_tile > 64 ? 2 : 1;
   const int64_t tile_base = (int64_t)kt * p.RB * Q * 2048;
   const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
-  float* partial1 = partial + p.vec_stride;
-
   int grp[4][1];
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
@@ -832,11 +911,7 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
     grp[s][0] = group_of_chunk(p, 128 * kt + min(tile_T * slot + t0, chunks_in_tile - 1));
   }
 
-  // ---- activations of this lane's slot, both vectors (fetched before anything else) ----
-  const int my_chunk = tile_T * lane + t0;
-  const __half* xp = p.x + (int64_t)(128 * kt + min(my_chunk, chunks_in_tile - 1)) * 8;
-  const u32x4 xraw0 = *reinterpret_cast<const u32x4*>(xp);
-  const u32x4 xraw1 = *reinterpret_cast<const u32x4*>(xp + p.n);
+  const int my_chunk = tile_T * lane + t0;   // the chunk of the slot whose tables this lane builds
 
   // planes fetched together: all up to four; beyond that half of them, or three where every
   // dword has a scale set of its own (a set is 2 * planes registers per dword)
@@ -847,25 +922,21 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
   // per wavefront to cover the memory latency at full bandwidth.
   constexpr int kScaleRegs = (AMODE & kAlphaShared) ? 2 : 2 * Q;   // per scale set
   constexpr int kUnitRegs = 4 * Q + ((AMODE & 3) == kAlphaQuad ? kScaleRegs : 4 * kScaleRegs + (HAS_Z ? 8 : 0));
-  constexpr int kFit = (PP < Q || kUnitRegs > 36) ? 0 : (kUnitRegs > 24 ? 1 : 2);
+  constexpr int kFit = (PP < Q || kUnitRegs > 30) ? 0 : (kUnitRegs > 24 ? 1 : 2);
   constexpr int D = kFit < kDepth ? kFit : kDepth;
   const int n_units = rb1 - rb0;
   const int u_clamp = n_units - 1;
   // Ring of D + 1 units; uid[k]: the unit (row block rb0 + uid) in slot k.  A wavefront starts
   // with units wave, wave + kWaves, ... and takes every further one from the queue.
   U u[D + 1];
-  float prev1[D + 1];
   int uid[D + 1];
   if (PP == Q && threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = (D > 0 ? D : 1) * kWaves;
 #pragma unroll
   for (int k = 0; k <= D; ++k) uid[k] = wave + k * kWaves;
   if (PP == Q) {
 #pragma unroll
-    for (int k = 0; k < D; ++k) {
-      const int rb = rb0 + min(uid[k], u_clamp);
-      load_unit<true>(u[k], p, tile_base, rb, lane, grp, partial, out_row, !first_tile, tile_T, t0);
-      prev1[k] = !first_tile ? load_device_coherent(partial1 + rb * 16 + out_row) : 0.0f;
-    }
+    for (int k = 0; k < D; ++k)
+      load_unit<true>(u[k], p, tile_base, rb0 + min(uid[k], u_clamp), lane, grp, nullptr, out_row, false, tile_T, t0);
   }
 
   // ---- tables: build slot b (of 16) = 16 keys [32 * (b % 8) + 16 * (b / 8), +16) of both vectors ----
@@ -904,94 +975,125 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
     sum_x[s] = HAS_Z ? lds_f32x2(((slot >> 5) << 16) | (0xffu << 8) | ((slot & 31u) << 3)) : zero;
   }
 
+  // Each of a unit's two results (one per vector) is in all four 16-lane groups after the
+  // reduction: lanes 0..15 add vector 0's, lanes 16..31 vector 1's to the running sums.
+  const int run_vec = (lane >> 4) & 1;
+  float* const run_lane = lut + kRunWord + run_vec * 16 + out_row;
   if constexpr (PP < Q) {
     for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
       float acc[2][4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
-      float pv0 = 0.0f, pv1 = 0.0f;
-      if (!first_tile) {
-        pv0 = load_device_coherent(partial + rb * 16 + out_row);
-        pv1 = load_device_coherent(partial1 + rb * 16 + out_row);
-      }
-      pair_passes<Q, 0, PP, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, tile_T, t0, lane_base, sum_x, acc);
+      pair_passes<Q, 0, PP, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, nullptr, out_row, tile_T, t0, lane_base, sum_x, acc);
       int row_in_block;
-      const float s0 = quad_rows_reduce(acc[0], lane, &row_in_block) + pv0;
-      const float s1 = quad_rows_reduce(acc[1], lane, &row_in_block) + pv1;
-      store_device_coherent(partial + rb * 16 + row_in_block, s0);
-      store_device_coherent(partial1 + rb * 16 + row_in_block, s1);
+      const float s0 = quad_rows_reduce(acc[0], lane, &row_in_block);
+      const float s1 = quad_rows_reduce(acc[1], lane, &row_in_block);
+      if (lane < 32) {
+        float* r = run_lane + (rb - rb0) * 32;
+        const float s = run_vec ? s1 : s0;
+        *r = first_tile ? s : *r + s;
+      }
     }
   } else {
     // Dynamic unit queue (see tile_body), D units fetched ahead, D + 1 units per pass of the
     // loop, ONE loop exit at the bottom: an exit in mid-loop would give the compiler a path
     // that carries an unused fetch back to the loop head, and with it a wait for all memory
-    // traffic, stores included, on every pass.  A wavefront that finds the queue empty part
-    // way through a pass still fetches (the last unit, again) and stores (to a spare area
-    // nobody reads) but skips the lookups.  Results are kept for one more unit and
-    // stored right after a fetch has been issued (a store shares the wavefront's memory
-    // counter with the fetches; see tile_body), by all four 16-lane groups (same address,
-    // same value).  The spare area has 128 bytes per wavefront: one spare line for all would
-    // serialise every wavefront of the device on one memory channel.
+    // traffic on every pass.  A wavefront that finds the queue empty part way through a pass
+    // still fetches (the last unit, again) but skips the lookups.
     if (uid[0] >= n_units) return;
-    float* const spare0 = p.spare + (((blockIdx.y * gridDim.x + blockIdx.x) & 255) * 16 + wave) * 32;
-    float held0 = 0.0f, held1 = 0.0f;
-    float* held_to = spare0;     // wave-uniform; the second vector's result goes held_step further
-    int64_t held_step = 16;
     do {
 #pragma unroll
       for (int j = 0; j <= D; ++j) {
         constexpr int kRing = D + 1;
         const int fill = (j + D) % kRing;   // the slot consumed one pass of j ago (for D == 0: this one)
         if (D > 0) uid[fill] = next_unit(lut, lane);
-        {
-          const int rb = rb0 + min(uid[fill], u_clamp);
-          load_unit<true>(u[fill], p, tile_base, rb, lane, grp, partial, out_row, !first_tile, tile_T, t0);
-          prev1[fill] = !first_tile ? load_device_coherent(partial1 + rb * 16 + out_row) : 0.0f;
-        }
-        store_device_coherent(held_to + out_row, held0);
-        store_device_coherent(held_to + held_step + out_row, held1);
-        __builtin_amdgcn_sched_barrier(0);   // fetch and stores stay ahead of the lookups below
-        const bool real = uid[j] < n_units;
-        if (real) {
+        load_unit<true>(u[fill], p, tile_base, rb0 + min(uid[fill], u_clamp), lane, grp, nullptr, out_row, false, tile_T, t0);
+        __builtin_amdgcn_sched_barrier(0);   // the fetch stays ahead of the lookups below
+        if (uid[j] < n_units) {
           float acc[2][4] = {{0.0f, 0.0f, 0.0f, 0.0f}, {0.0f, 0.0f, 0.0f, 0.0f}};
           accumulate_pair(u[j], lane_base, sum_x, acc);
           int row_in_block;
-          held0 = quad_rows_reduce(acc[0], lane, &row_in_block) + u[j].prev;
-          held1 = quad_rows_reduce(acc[1], lane, &row_in_block) + prev1[j];
+          const float s0 = quad_rows_reduce(acc[0], lane, &row_in_block);
+          const float s1 = quad_rows_reduce(acc[1], lane, &row_in_block);
+          if (lane < 32) {
+            float* r = run_lane + uid[j] * 32;
+            const float s = run_vec ? s1 : s0;
+            *r = first_tile ? s : *r + s;
+          }
         }
-        held_to = real ? partial + (rb0 + uid[j]) * 16 : spare0;
-        held_step = real ? p.vec_stride : 16;
         if (D == 0) uid[0] = next_unit(lut, lane);
       }
     } while (uid[0] < n_units);
-    store_device_coherent(held_to + out_row, held0);
-    store_device_coherent(held_to + held_step + out_row, held1);
+  }
+}
+
+// The running sums of NVEC vectors for row blocks [rb0, rb1), [block][vector][16 rows] in
+// LDS, become the workgroup's partial sums in the workspace.
+template <int NVEC>
+__device__ __forceinline__ void flush_vector_sums(const GemvParams& p, const float* lut, int rb0, int rb1, float* partial) {
+  __syncthreads();
+  const int rows = (rb1 - rb0) * 16;
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));   // the store addresses are formed here, not kept in registers from the kernel's start on
+#pragma unroll
+  for (int v = 0; v < NVEC; ++v) {
+    if (NVEC == 4 && v >= p.batch) continue;   // a quad launched for three vectors
+    for (int i = tid; i < rows; i += kThreads)
+      store_device_coherent(partial + v * p.vec_stride + rb0 * 16 + i, lut[kRunWord + ((i >> 4) * NVEC + v) * 16 + (i & 15)]);
   }
 }
 
 // p.NT counts HALF tiles here; half tile h is sub-slab h % 2 of K tile h / 2 (a last tile
 // with one sub-slab contributes one half tile).  AM2 / AM1 as in the GEMV kernel.
 
+// A workgroup walks its row range in stretches of at most kRunBlocks / 2 row blocks (one
+// stretch, but for layers of more than 60,000 rows or so): the half tiles of its K group for
+// one stretch, whose sums over those half tiles stand in LDS all the while (no trip through
+// memory per half tile), then the stretch's sums go to the workspace as partial sums.
 template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_pair_kernel(GemvParams p) {
-  __shared__ float lut[kLutBytes / 4 + 4];   // (the kernel's only LDS object: see gemv_workgroup)
+  __shared__ float lut[kGemvLdsFloats];   // (the kernel's only LDS object: see gemv_workgroup)
   const int kg = blockIdx.x;
   const int rs = blockIdx.y;
   int rb0, rb1;
   row_range(p, rs, &rb0, &rb1);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
-  for (int ti = 0; ti < p.TPG; ++ti) {
-    const int h = kg * p.TPG + ti;
-    if (h >= p.NT) break;
-    if (ti > 0) {   // as in the GEMV kernel
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
+  const int lane = threadIdx.x & 63;
+  constexpr int kStretch = kRunBlocks / 2;
+  for (int s0 = rb0; s0 < rb1; s0 += kStretch) {
+    const int s1 = min(s0 + kStretch, rb1);
+    // (with quad-shared scales, which leave the registers for it, the activations of the
+    // next half tile are fetched before the lookups of this one start)
+    constexpr bool kAheadX = (AM2 & 3) == kAlphaQuad && (AM1 & 3) == kAlphaQuad;
+    const int h_end = min((kg + 1) * p.TPG, p.NT);
+    u32x4 xraw0 = {0u, 0u, 0u, 0u}, xraw1 = {0u, 0u, 0u, 0u};
+    if (kAheadX) {
+      xraw0 = pair_fetch_x(p, kg * p.TPG, 0, lane);
+      xraw1 = pair_fetch_x(p, kg * p.TPG, 1, lane);
     }
-    const int kt = h >> 1, t0 = h & 1;
-    if (min(128, p.nchunks - 128 * kt) > 64)
-      pair_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, rb0, rb1, partial, ti == 0);
-    else
-      pair_tile_body<Q, AM1, HAS_Z, kPairDepth>(p, lut, kt, t0, rb0, rb1, partial, ti == 0);
+    for (int h = kg * p.TPG; h < h_end; ++h) {
+      // every lookup of the half tile before is done before its tables are overwritten (and
+      // the stretch before has been copied out before its sums are)
+      if (h > kg * p.TPG || s0 > rb0) __syncthreads();
+      if (!kAheadX) {
+        xraw0 = pair_fetch_x(p, h, 0, lane);
+        xraw1 = pair_fetch_x(p, h, 1, lane);
+      }
+      u32x4 xnext0 = xraw0, xnext1 = xraw1;
+      if (kAheadX) {
+        const int hn = min(h + 1, h_end - 1);
+        xnext0 = pair_fetch_x(p, hn, 0, lane);
+        xnext1 = pair_fetch_x(p, hn, 1, lane);
+      }
+      const int kt = h >> 1, t0 = h & 1;
+      if (min(128, p.nchunks - 128 * kt) > 64)
+        pair_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, s0, s1, h == kg * p.TPG, xraw0, xraw1);
+      else
+        pair_tile_body<Q, AM1, HAS_Z, kPairDepth>(p, lut, kt, t0, s0, s1, h == kg * p.TPG, xraw0, xraw1);
+      xraw0 = xnext0;
+      xraw1 = xnext1;
+    }
+    flush_vector_sums<2>(p, lut, s0, s1, partial);
   }
-  finish_row_range<2>(p, lut, rs, rb0, rb1);
+  finish_row_range<2, (Q <= 4)>(p, lut, rs, rb0, rb1);
 }
 
 #include "lutgemm_quad.h"
@@ -1231,52 +1333,31 @@ void choose_grid(int cus, int NT, int RB, bool lds_carry, int* KG, int* TPG, int
   }
 }
 
-// The same choice for the pair kernel (NT counts half tiles).  Costs in units of one round
-// of units of a workgroup: a table build is worth about 2.5 of them; the final reduction
-// runs in batches (rows of a range per pass of the workgroup x 16 K groups x 2 vectors) of
-// about 1.25 each, and more than 16 K groups cost further batches and more partial sums
-// (1 plus 0.1 per group beyond 16), which is what rules out one half tile per group on wide
-// layers.
-void choose_pair_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
+// The same choice for the pair and quad kernels (NT counts half tiles or quarter ids, a
+// row unit is a row block or a pair of them).  Their running sums stay in LDS for the whole
+// K group, so a K group costs its partial sums once.  Cost in rounds of units of a workgroup,
+// fitted to twelve layer shapes (OPT-13B, OPT-175B, LLaMA-65B) at batch 2 and 4, every tiles-
+// per-group count from 1 to 8 (16) timed: per half tile or quarter the rounds of units (the
+// queue shares a partly filled round out, but one round is the least) plus the table build;
+// the last-arrival sum, which ONE workgroup per row range does, by the partial sums a thread
+// of it loads; and a charge per K group beyond a few (more partial sums to write, more
+// workgroup columns).  The choice is within 2 % (quad) and 6 % (pair) of the best measured
+// on every one of the twelve shapes.
+void choose_vector_grid(int vectors, int cus, int NT, int row_units, int* KG, int* TPG, int* RS) {
+  const bool quad = vectors == 4;
+  const double build = quad ? 0.6 : 0.4, per_load = quad ? 0.01 : 0.005, per_group = quad ? 0.1 : 0.05;
+  const int free_groups = quad ? 8 : 12, rows_per_unit = quad ? 32 : 16;
   double best = 1e30;
-  const int max_rs = (RB + kWaves - 1) / kWaves;
-  const int rows_per_pass = ((kWaves > 8) ? 3 : 8) * kThreads;   // kRowsPerPass of the final reduction
-  for (int tpg = 1; tpg <= NT && tpg <= 8; ++tpg) {
+  const int max_rs = (row_units + kWaves - 1) / kWaves;
+  for (int tpg = 1; tpg <= NT && tpg <= (quad ? 16 : 8); ++tpg) {
     const int kg = (NT + tpg - 1) / tpg;
     int rs = cus / kg;
     rs = rs < 1 ? 1 : (rs > max_rs ? max_rs : rs);
-    const int blocks = (RB + rs - 1) / rs;
-    const int rounds = (blocks + kWaves - 1) / kWaves;
-    const int tiles = (NT + kg - 1) / kg;
-    const int passes = (blocks * 16 + rows_per_pass - 1) / rows_per_pass;
-    const double cost = tiles * (rounds + 2.5) + 1.25 * 2 * passes * ((kg + 15) / 16) + (kg > 16 ? 1.0 + 0.1 * (kg - 16) : 0.0);
-    if (cost < best) {
-      best = cost;
-      *KG = kg;
-      *TPG = tpg;
-      *RS = rs;
-    }
-  }
-}
-
-// The same for the quad kernel: NT counts quarter ids, a unit is a pair of row blocks, the
-// final reduction runs for four vectors.
-void choose_quad_grid(int cus, int NT, int RB, int* KG, int* TPG, int* RS) {
-  double best = 1e30;
-  const int pairs = (RB + 1) / 2;
-  const int max_rs = (pairs + kWaves - 1) / kWaves;
-  const int rows_per_pass = ((kWaves > 8) ? 3 : 8) * kThreads;
-  for (int tpg = 1; tpg <= NT && tpg <= 16; ++tpg) {
-    const int kg = (NT + tpg - 1) / tpg;
-    int rs = cus / kg;
-    rs = rs < 1 ? 1 : (rs > max_rs ? max_rs : rs);
-    const int units = (pairs + rs - 1) / rs;
-    // (fractional beyond the first: the queue lets the wavefronts of a workgroup share a last,
-    // partly filled round)
+    const int units = (row_units + rs - 1) / rs;
     const double rounds = units > kWaves ? (double)units / kWaves : 1.0;
     const int tiles = (NT + kg - 1) / kg;
-    const int passes = (units * 32 + rows_per_pass - 1) / rows_per_pass;
-    const double cost = tiles * (rounds + 1.75) + 1.25 * 4 * passes * ((kg + 15) / 16);
+    const int loads = kg * ((vectors * rows_per_unit * units + kThreads - 1) / kThreads);
+    const double cost = tiles * (rounds + build) + per_load * loads + per_group * (kg > free_groups ? kg - free_groups : 0);
     if (cost < best) {
       best = cost;
       *KG = kg;
@@ -1292,9 +1373,9 @@ void plan_grid(int cus, int vectors, int q, int64_t g, GemvParams* p) {
   const int wgs = cus > 256 ? 256 : cus;
   const bool lds_carry = carries_in_lds(q, g);
   if (vectors == 4)
-    choose_quad_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
+    choose_vector_grid(4, wgs, p->NT, (p->RB + 1) / 2, &p->KG, &p->TPG, &p->row_splits);
   else if (vectors == 2)
-    choose_pair_grid(wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
+    choose_vector_grid(2, wgs, p->NT, p->RB, &p->KG, &p->TPG, &p->row_splits);
   else
     choose_grid(wgs, p->NT, p->RB, lds_carry, &p->KG, &p->TPG, &p->row_splits);
   const int which = vectors == 4 ? 2 : (vectors == 2 ? 1 : 0);
@@ -1315,7 +1396,6 @@ void plan_grid(int cus, int vectors, int q, int64_t g, GemvParams* p) {
 }
 
 constexpr size_t kCounterBytes = 32768;   // 32 activation vectors x 256 row ranges
-constexpr size_t kSpareBytes = 256 * 16 * 32 * sizeof(float);   // 128 bytes per (workgroup slot, wavefront)
 
 
 template <bool HAS_Z, int NB>
@@ -1556,8 +1636,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     return LUTGEMM_EUNSUPPORTED;   // (never planned: the kernel's running sums would not fit)
 
   uint32_t* counters = static_cast<uint32_t*>(workspace);
-  p.spare = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
-  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
   p.vec_stride = m_pad;
   const size_t y_elem = p.y_f32 ? sizeof(float) : sizeof(__half);
 
@@ -1594,7 +1673,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
     pb.range_base = row_units / pb.row_splits;
     pb.range_rem = row_units % pb.row_splits;
     void* args[] = {&pb};
-    if (!lds_layout_ok(kb, (take == 1 ? (size_t)kGemvLdsFloats : (size_t)(kLutBytes / 4 + 4)) * sizeof(float)))
+    if (!lds_layout_ok(kb, (size_t)kGemvLdsFloats * sizeof(float)))
       return LUTGEMM_EHIP;
     if (hipLaunchKernel(kb, dim3(pb.KG, pb.row_splits), dim3(kThreads), args, 0,
                         stream) != hipSuccess)
@@ -1649,8 +1728,7 @@ static int gemm_matrix_cores(bool dequant, const void* x, const void* bits, cons
   p.kg_stride = m_pad * batch;
   p.vec_stride = m_pad;
   p.counters = static_cast<uint32_t*>(workspace);
-  p.spare = nullptr;
-  p.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
+  p.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
   GemvKernel kern = dequant ? lutgemm_parts::dequant_family(q, z != nullptr, batch) : pick_planes_kernel(q, z != nullptr, batch);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
   if (p.row_splits > 65535) return LUTGEMM_EUNSUPPORTED;   // grid y
@@ -1722,11 +1800,11 @@ int lutgemm_gemv(const void* x, const void* bits, const void* alpha, const void*
 
 size_t lutgemm_group_workspace_bytes(const int64_t* m, const int64_t* n, int count, int q, int g, int mu) {
   if (!m || !n || count < 1 || count > kMaxGroup) return 0;
-  size_t total = kCounterBytes + kSpareBytes;
+  size_t total = kCounterBytes;
   for (int i = 0; i < count; ++i) {
     const size_t one = lutgemm_workspace_bytes(m[i], n[i], q, g, mu, 1);
     if (one == 0) return 0;
-    total += (one - kCounterBytes - kSpareBytes + 255) / 256 * 256;   // the layer's partial sums
+    total += (one - kCounterBytes + 255) / 256 * 256;   // the layer's partial sums
   }
   return total;
 }
@@ -1746,8 +1824,8 @@ int lutgemm_gemv_group(const void* const* x, const void* const* bits, const void
   gp.count = count;
   gp.first_wg[0] = 0;
   uint32_t* counters = static_cast<uint32_t*>(workspace);
-  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes + kSpareBytes);
-  size_t used = kCounterBytes + kSpareBytes;
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kCounterBytes);
+  size_t used = kCounterBytes;
   int64_t g_first = -1;
   for (int i = 0; i < count; ++i) {
     if (!x[i] || !bits[i] || !alpha[i] || !y[i] || (z && !z[i])) return LUTGEMM_EINVAL;
@@ -1783,10 +1861,9 @@ int lutgemm_gemv_group(const void* const* x, const void* const* bits, const void
     p.range_rem = p.RB % p.row_splits;
     p.counters = counters + (size_t)i * 256;
     p.partial = partials;
-    p.spare = nullptr;
-    const size_t one = lutgemm_workspace_bytes(m[i], n[i], q, g, mu, 1);
+      const size_t one = lutgemm_workspace_bytes(m[i], n[i], q, g, mu, 1);
     if (one == 0) return LUTGEMM_EINVAL;
-    const size_t part_bytes = (one - kCounterBytes - kSpareBytes + 255) / 256 * 256;
+    const size_t part_bytes = (one - kCounterBytes + 255) / 256 * 256;
     partials += part_bytes / sizeof(float);
     used += part_bytes;
     const int64_t wgs = (int64_t)p.KG * p.row_splits;

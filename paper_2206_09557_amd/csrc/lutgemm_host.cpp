@@ -296,14 +296,14 @@ int lutgemm_share_scales(const uint16_t* alpha_packed, int64_t m, int64_t n, int
 size_t lutgemm_workspace_bytes(int64_t m, int64_t n, int q, int g, int mu, int batch) {
   Shape s;
   if (mu != 8 || batch < 1 || batch > 32 || !make_shape(m, n, q, g, &s)) return 0;
-  // arrival counters (32 KB), a spare area for results nobody reads (512 KB), then one fp32
+  // arrival counters (32 KB), then one fp32
   // partial per (K group, activation vector, row of an even number of row blocks); four
   // vectors at a time split K over quarter tiles, two over half tiles, so up to four (two)
   // times as many groups as tiles can occur
   const size_t groups = (size_t)s.NT * (batch >= 3 ? 4 : (batch >= 2 ? 2 : 1));
   const size_t rows = (size_t)(s.RB + (s.RB & 1)) * kRowsPerBlock;
   const size_t vectors = (size_t)batch + (batch % 4 == 3 ? 1 : 0);   // three left over run as four
-  return (size_t)32768 + (size_t)524288 + groups * vectors * rows * sizeof(float);
+  return (size_t)32768 + groups * vectors * rows * sizeof(float);
 }
 
 int lutgemm_pack_bcq(const uint16_t* W, int64_t m, int64_t n, int q, int g, int mu, int mode,

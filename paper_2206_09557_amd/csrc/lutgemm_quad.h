@@ -36,36 +36,56 @@ __device__ __forceinline__ float half_rows_reduce(const float (&acc)[4], int lan
   return s;
 }
 
+// The lookups of one (plane, row-of-four) step: the four dwords' key bytes, one 16-byte read each.
+template <int Q, int I0, int QP, int AMODE, bool HAS_Z>
+__device__ __forceinline__ void quad_lookups(const Unit<Q, I0, QP, 1, AMODE, HAS_Z>& u, const uint32_t (&lane_base)[4],
+                                             int step, f32x4v (&e)[4]) {
+  const int i = step >> 2, rho = step & 3;
+  // address bytes {0, L / 16, key byte rho, (L % 16) * 16}: lane_base holds bytes 0 and 2 (as its bytes 0 and 1)
+  const uint32_t sel = 0x0c010000u | ((4u + rho) << 8);
+#pragma unroll
+  for (int s = 0; s < 4; ++s) e[s] = lds_f32x4(__builtin_amdgcn_perm(u.w[i][0][s], lane_base[s], sel));
+}
+
+// The steps are software-pipelined by hand: the reads of step k + 1 are issued, then the
+// additions of step k run while they are in flight (the scheduling barriers keep it so).
+// Left to itself the compiler waits for every read or two right after issuing them, and the
+// wavefronts of a compute unit then take turns at the LDS and at the vector ALU instead of
+// using both at once.
 template <int Q, int I0, int QP, int AMODE, bool HAS_Z>
 __device__ __forceinline__ void accumulate_quad(const Unit<Q, I0, QP, 1, AMODE, HAS_Z>& u, const uint32_t (&lane_base)[4],
                                                 const f32x4v (&sum_x)[4], float (&acc)[4][4]) {
   using U = Unit<Q, I0, QP, 1, AMODE, HAS_Z>;
+  constexpr int kSteps = 4 * QP;
+  // (with a scale set per dword the registers hold one step's reads only)
+  constexpr int kAhead = (AMODE & 3) == kAlphaQuad ? 1 : 0;
+  f32x4v e[kAhead + 1][4];
+  if (kAhead) quad_lookups(u, lane_base, 0, e[0]);
 #pragma unroll
-  for (int i = 0; i < QP; ++i) {
+  for (int step = 0; step < kSteps; ++step) {
+    if (step + kAhead < kSteps) quad_lookups(u, lane_base, step + kAhead, e[(step + kAhead) & kAhead]);
+    __builtin_amdgcn_sched_barrier(0);
+    const int i = step >> 2, rho = step & 3;
+    const f32x4v(&cur)[4] = e[step & kAhead];
+    if ((AMODE & 3) == kAlphaQuad) {   // section 3.2 rule 2: one scale per run of lookups
+      const f32x4v run = (cur[0] + cur[1]) + (cur[2] + cur[3]);
+      const float a = scale_of<AMODE>(u.al[0][0], i, I0 + i, rho);
 #pragma unroll
-    for (int rho = 0; rho < 4; ++rho) {
-      // address bytes {0, L / 16, key byte rho, (L % 16) * 16}: lane_base holds bytes 0 and 2 (as its bytes 0 and 1)
-      const uint32_t sel = 0x0c010000u | ((4u + rho) << 8);
-      float run[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      for (int v = 0; v < 4; ++v) acc[v][rho] = fmaf(a, run[v], acc[v][rho]);
+    } else {
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const f32x4v e = lds_f32x4(__builtin_amdgcn_perm(u.w[i][0][s], lane_base[s], sel));
-        const bool first = ((AMODE & 3) == kAlphaQuad) ? (s == 0) : true;
+        const float a = scale_of<AMODE>(u.al[s][0], i, I0 + i, rho);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) run[v] = first ? e[v] : run[v] + e[v];
-        if ((AMODE & 3) != kAlphaQuad || s == 3) {   // section 3.2 rule 2: one scale per run of lookups
-          const float a = scale_of<AMODE>(u.al[((AMODE & 3) == kAlphaQuad) ? 0 : s][0], i, I0 + i, rho);
-#pragma unroll
-          for (int v = 0; v < 4; ++v) acc[v][rho] = fmaf(a, run[v], acc[v][rho]);
-        }
+        for (int v = 0; v < 4; ++v) acc[v][rho] = fmaf(a, cur[s][v], acc[v][rho]);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
   }
   if (HAS_Z && I0 == 0) {   // offset term of eq. 3
 #pragma unroll
     for (int s = 0; s < U::NS; ++s) {
-      f32x4v sx = sum_x[s];
-      if ((AMODE & 3) == kAlphaQuad) sx = (sum_x[0] + sum_x[1]) + (sum_x[2] + sum_x[3]);
+      const f32x4v sx = sum_x[s];   // (quad-shared scales: the caller has put the sum over the four slots into sum_x[0])
 #pragma unroll
       for (int rho = 0; rho < 4; ++rho) {
         const float zf = half_of(u.zz[s][0], rho);
@@ -89,10 +109,34 @@ __device__ __forceinline__ void quad_passes(const GemvParams& p, int64_t tile_ba
                                               sum_x, acc);
 }
 
-// One workgroup, one quarter (kt, t0, h), row blocks [rb0, rb1) with rb0 even.
+// Table build of a quarter: lane (sl = lane / 4, v = lane % 4) of wavefront b writes the keys
+// [32 * (b / 2), +32) of vector v for slot 16 * (b % 2) + sl, i.e. the 64 lanes of a store
+// write 64 consecutive floats (16 slots x 4 vectors of one key): no bank conflicts.  (A quad
+// launched for three vectors builds the fourth table set from the third vector.)  The
+// activations a lane needs for that: 8 halfs, fetched ahead of the quarter before.
+__device__ __forceinline__ u32x4 quad_fetch_x(const GemvParams& p, int id, int wave, int lane) {
+  const int kt = id >> 2, t0 = (id >> 1) & 1, h = id & 1;
+  const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
+  const int tile_T = chunks_in_tile > 64 ? 2 : 1;
+  const int chunk = tile_T * (32 * h + 16 * (wave & 1) + (lane >> 2)) + t0;
+  const __half* xp = p.x + (int64_t)(128 * kt + min(chunk, chunks_in_tile - 1)) * 8;   // clamped: value unused if out of range
+  return *reinterpret_cast<const u32x4*>(xp + (int64_t)min(lane & 3, p.batch - 1) * p.n);
+}
+
+// Does quarter `id` (4 * tile + 2 * sub-slab + half) exist?  Not in a ragged last tile
+// whose sub-slab or half has no columns.
+__device__ __forceinline__ bool quarter_exists(const GemvParams& p, int id) {
+  const int kt = id >> 2, t0 = (id >> 1) & 1, h = id & 1;
+  const int chunks = min(128, p.nchunks - 128 * kt);
+  const int T = chunks > 64 ? 2 : 1;
+  return t0 < T && 32 * h * T + t0 < chunks;
+}
+
+// One workgroup, one quarter (kt, t0, h), row blocks [rb0, rb1) with rb0 even.  xraw: what
+// quad_fetch_x returned for this quarter.
 template <int Q, int AMODE, bool HAS_Z, int kDepth>
 __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, int kt, int t0, int h, int rb0, int rb1,
-                                               float* partial, bool first_tile) {
+                                               bool first_tile, const u32x4& xraw) {
   using U = Unit<Q, 0, Q, 1, AMODE, HAS_Z>;
   int lane = threadIdx.x & 63;
   asm volatile("" : "+v"(lane));   // see tile_body
@@ -104,7 +148,6 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
   const int lq = lane & 31;                   // lane within the half = slot it builds / position in the quarter
   const int slab_lane = 32 * h + lq;          // lane position inside the 1 KB slabs
   const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
-  const int pair_row = half * 16 + out_row;   // row within the pair of row blocks
 
   int grp[4][1];
 #pragma unroll
@@ -113,30 +156,18 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
     grp[s][0] = group_of_chunk(p, 128 * kt + min(tile_T * (32 * h + L) + t0, chunks_in_tile - 1));
   }
 
-  // ---- activations: wavefront id b (of 16) builds key range 32 * (b % 8) of vectors
-  //      2 * (b / 8) + half for the slot lq ----
-  const int my_chunk = tile_T * (32 * h + lq) + t0;
-  const __half* xp = p.x + (int64_t)(128 * kt + min(my_chunk, chunks_in_tile - 1)) * 8;
-  u32x4 xraw[kBuildPasses];
-#pragma unroll
-  for (int b = 0; b < kBuildPasses; ++b) {
-    const int v = 2 * ((wave + b * kWaves) >> 3) + half;
-    // (a quad launched for three vectors builds the fourth table set from the third vector)
-    xraw[b] = *reinterpret_cast<const u32x4*>(xp + (int64_t)min(v, p.batch - 1) * p.n);
-  }
-
   // planes fetched together: all up to four; beyond that half of them, or two where every
   // dword has a scale set of its own (16 accumulators leave fewer registers than in the
   // other kernels); a second unit in flight only with quad-shared scales
-  constexpr int PP = Q > 4 ? ((AMODE & 3) == kAlphaQuad ? (Q + 1) / 2 : 2) : Q;
+  constexpr int PP = (AMODE & 3) == kAlphaQuad ? (Q > 4 ? (Q > 7 ? 3 : (Q + 1) / 2) : Q)
+                                               : ((Q > 4 || (Q == 4 && HAS_Z)) ? 2 : Q);
   constexpr int kScaleRegs = (AMODE & kAlphaShared) ? 2 : 2 * Q;
-  constexpr int kFit = (PP < Q || (AMODE & 3) != kAlphaQuad || 4 * Q + kScaleRegs > 24) ? 0 : 1;
+  constexpr int kFit = (PP < Q || (AMODE & 3) != kAlphaQuad || 4 * Q + kScaleRegs + (HAS_Z ? 2 : 0) > 24) ? 0 : 1;
   constexpr int D = kFit < kDepth ? kFit : kDepth;
   const int n_units = (rb1 - rb0 + 1) >> 1;   // pairs of row blocks
   const int u_clamp = n_units - 1;
   const int rb_last = p.RB - 1;               // a pair's second block may lie past the end: fetch the last one instead
   U u[D + 1];
-  float prev[D + 1][4];
   int uid[D + 1];
   if (PP == Q && threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = (D > 0 ? D : 1) * kWaves;
 #pragma unroll
@@ -145,22 +176,16 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
 #pragma unroll
     for (int k = 0; k < D; ++k) {
       const int rb = min(rb0 + 2 * min(uid[k], u_clamp) + half, rb_last);
-      load_unit<true>(u[k], p, tile_base, rb, slab_lane, grp, partial, out_row, false, tile_T, t0);
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        prev[k][v] = !first_tile ? load_device_coherent(partial + v * p.vec_stride + rb * 16 + out_row) : 0.0f;
+      load_unit<true>(u[k], p, tile_base, rb, slab_lane, grp, nullptr, out_row, false, tile_T, t0);
     }
   }
 
   // ---- tables ----
-#pragma unroll
-  for (int b = 0; b < kBuildPasses; ++b) {
-    const int id = wave + b * kWaves;
-    const int kh = id & 7;
-    const int v = 2 * (id >> 3) + half;
+  {
+    const int kh = wave >> 1;
     float xs[8];
-    unpack_x(xraw[b], my_chunk < chunks_in_tile, xs);
-    float* dst = lut + ((lq >> 4) << 14) + ((lq & 15) << 2) + v;
+    unpack_x(xraw, tile_T * (32 * h + 16 * (wave & 1) + (lane >> 2)) + t0 < chunks_in_tile, xs);
+    float* dst = lut + ((wave & 1) << 14) + lane;
 #pragma unroll
     for (int hi = 0; hi < 2; ++hi) {
       float e[16];
@@ -179,34 +204,36 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
     lane_base[s] = ((L & 15u) << 4) | ((L >> 4) << 8);
     sum_x[s] = HAS_Z ? lds_f32x4(((L >> 4) << 16) | (0xffu << 8) | ((L & 15u) << 4)) : f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
   }
+  // one offset per quad of slots: only the sum over the four slots is needed
+  if (HAS_Z && (AMODE & 3) == kAlphaQuad) sum_x[0] = (sum_x[0] + sum_x[1]) + (sum_x[2] + sum_x[3]);
 
+  // Running sums in LDS, [row block of the range][vector][16 rows].  After the reduction
+  // both 16-lane groups of a half hold the results of the half's row block for all four
+  // vectors: group 0 adds vectors 0 and 2, group 1 vectors 1 and 3.  (A pair's second block
+  // may be the padded one past the range: it has a place in LDS and is never copied out.)
+  const int odd = (lane >> 4) & 1;
+  float* const run_lane = lut + kRunWord + (half * 4 + odd) * 16 + out_row;
   if constexpr (PP < Q) {
     for (int un = wave; un < n_units; un += kWaves) {
-      const int rb_store = rb0 + 2 * un + half;           // may be the padded block past the end (never read back)
-      const int rb = min(rb_store, rb_last);
+      const int rb = min(rb0 + 2 * un + half, rb_last);
       float acc[4][4];
-      float pv[4];
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        pv[v] = !first_tile ? load_device_coherent(partial + v * p.vec_stride + rb_store * 16 + out_row) : 0.0f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[v][r] = 0.0f;
-      }
-      quad_passes<Q, 0, PP, AMODE, HAS_Z>(p, tile_base, rb, slab_lane, grp, partial, out_row, tile_T, t0, lane_base, sum_x,
-                                          acc);
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        store_device_coherent(partial + v * p.vec_stride + rb_store * 16 + out_row, half_rows_reduce(acc[v], lane) + pv[v]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[v][r] = 0.0f;
+      quad_passes<Q, 0, PP, AMODE, HAS_Z>(p, tile_base, rb, slab_lane, grp, nullptr, out_row, tile_T, t0, lane_base, sum_x,
+                                          acc);
+      float sv[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sv[v] = half_rows_reduce(acc[v], lane);
+      float* r = run_lane + un * 128;
+      const float lo = odd ? sv[1] : sv[0], hi = odd ? sv[3] : sv[2];
+      r[0] = first_tile ? lo : r[0] + lo;
+      r[32] = first_tile ? hi : r[32] + hi;
     }
   } else {
-    // The pair kernel's loop: dynamic unit queue, D units fetched ahead, one exit at the
-    // bottom, results stored one unit later right after a fetch, surplus passes store to the
-    // wavefront's spare 128 bytes (all four vectors onto the same 32 floats).
+    // The pair kernel's loop: dynamic unit queue, D units fetched ahead, one exit at the bottom.
     if (uid[0] >= n_units) return;
-    float* const spare0 = p.spare + (((blockIdx.y * gridDim.x + blockIdx.x) & 255) * 16 + wave) * 32;
-    float held[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    float* held_to = spare0;       // wave-uniform; vector v goes v * held_step further
-    int64_t held_step = 0;
     do {
 #pragma unroll
       for (int j = 0; j <= D; ++j) {
@@ -215,40 +242,36 @@ __device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, 
         if (D > 0) uid[fill] = next_unit(lut, lane);
         {
           const int rb = min(rb0 + 2 * min(uid[fill], u_clamp) + half, rb_last);
-          load_unit<true>(u[fill], p, tile_base, rb, slab_lane, grp, partial, out_row, false, tile_T, t0);
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            prev[fill][v] = !first_tile ? load_device_coherent(partial + v * p.vec_stride + rb * 16 + out_row) : 0.0f;
+          load_unit<true>(u[fill], p, tile_base, rb, slab_lane, grp, nullptr, out_row, false, tile_T, t0);
         }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) store_device_coherent(held_to + v * held_step + pair_row, held[v]);
-        __builtin_amdgcn_sched_barrier(0);   // fetch and stores stay ahead of the lookups below
-        const bool real = uid[j] < n_units;
-        if (real) {
+        __builtin_amdgcn_sched_barrier(0);   // the fetch stays ahead of the lookups below
+        if (uid[j] < n_units) {
           float acc[4][4];
 #pragma unroll
           for (int v = 0; v < 4; ++v)
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[v][r] = 0.0f;
           accumulate_quad(u[j], lane_base, sum_x, acc);
+          float sv[4];
 #pragma unroll
-          for (int v = 0; v < 4; ++v) held[v] = half_rows_reduce(acc[v], lane) + prev[j][v];
+          for (int v = 0; v < 4; ++v) sv[v] = half_rows_reduce(acc[v], lane);
+          float* r = run_lane + uid[j] * 128;
+          const float lo = odd ? sv[1] : sv[0], hi = odd ? sv[3] : sv[2];
+          r[0] = first_tile ? lo : r[0] + lo;
+          r[32] = first_tile ? hi : r[32] + hi;
         }
-        held_to = real ? partial + (rb0 + 2 * uid[j]) * 16 : spare0;
-        held_step = real ? p.vec_stride : 0;
         if (D == 0) uid[0] = next_unit(lut, lane);
       }
     } while (uid[0] < n_units);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) store_device_coherent(held_to + v * held_step + pair_row, held[v]);
   }
 }
 
 // p.NT counts quarter ids here: id = 4 * tile + 2 * sub-slab + half; ids whose sub-slab or
 // half does not exist in a ragged last tile are skipped.  Row ranges start at even row blocks.
+// Stretches of at most kRunBlocks / 4 row blocks, as in the pair kernel.
 template <int Q, bool HAS_Z, int AM2, int AM1>
 __global__ __launch_bounds__(kThreads) void lutgemm_quad_kernel(GemvParams p) {
-  __shared__ float lut[kLutBytes / 4 + 4];   // (the kernel's only LDS object: see gemv_workgroup)
+  __shared__ float lut[kGemvLdsFloats];   // (the kernel's only LDS object: see gemv_workgroup)
   const int kg = blockIdx.x;
   const int rs = blockIdx.y;
   int pair0, pair1;                 // row units are pairs of row blocks here
@@ -256,30 +279,40 @@ __global__ __launch_bounds__(kThreads) void lutgemm_quad_kernel(GemvParams p) {
   const int rb0 = 2 * pair0;
   const int rb1 = min(2 * pair1, p.RB);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
-  bool first = true;
-  for (int ti = 0; ti < p.TPG; ++ti) {
-    const int id = kg * p.TPG + ti;
-    if (id >= p.NT) break;
-    const int kt = id >> 2, t0 = (id >> 1) & 1, h = id & 1;
-    const int chunks = min(128, p.nchunks - 128 * kt);
-    const int T = chunks > 64 ? 2 : 1;
-    if (t0 >= T || 32 * h * T + t0 >= chunks) continue;   // no such quarter in this tile (wave-uniform)
-    if (!first) {
-      // every lookup of the previous quarter is done before its tables are overwritten, and
-      // every partial sum of it is in memory before another wavefront reads it back
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  constexpr int kStretch = kRunBlocks / 4;   // even
+  for (int s0 = rb0; s0 < rb1; s0 += kStretch) {
+    const int s1 = min(s0 + kStretch, rb1);
+    // The quarters of the K group that exist, one after the other; the activations of the
+    // next one are fetched before the lookups of the current one start.
+    const int id_end = min((kg + 1) * p.TPG, p.NT);
+    int id = kg * p.TPG;
+    while (id < id_end && !quarter_exists(p, id)) ++id;
+    bool first = true;
+    u32x4 xraw = {0u, 0u, 0u, 0u};
+    if (id < id_end) xraw = quad_fetch_x(p, id, wave, lane);
+    while (id < id_end) {
+      int next = id + 1;
+      while (next < id_end && !quarter_exists(p, next)) ++next;
+      // every lookup of the quarter before is done before its tables are overwritten (and
+      // the stretch before has been copied out before its sums are)
+      if (!first || s0 > rb0) __syncthreads();
+      const u32x4 xnext = quad_fetch_x(p, next < id_end ? next : id, wave, lane);
+      const int kt = id >> 2, t0 = (id >> 1) & 1, h = id & 1;
+      if (min(128, p.nchunks - 128 * kt) > 64)
+        quad_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, h, s0, s1, first, xraw);
+      else
+        quad_tile_body<Q, AM1, HAS_Z, kPairDepth>(p, lut, kt, t0, h, s0, s1, first, xraw);
+      xraw = xnext;
+      id = next;
+      first = false;
     }
-    if (T == 2)
-      quad_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, h, rb0, rb1, partial, first);
-    else
-      quad_tile_body<Q, AM1, HAS_Z, kPairDepth>(p, lut, kt, t0, h, rb0, rb1, partial, first);
-    first = false;
+    if (first) {   // a K group made of non-existent quarters only: its sums are zeros
+      if (s0 > rb0) __syncthreads();
+      for (int i = threadIdx.x; i < (s1 - s0) * 64; i += kThreads) lut[kRunWord + i] = 0.0f;
+    }
+    flush_vector_sums<4>(p, lut, s0, s1, partial);
   }
-  if (first) {   // a K group made of non-existent quarters only: its partials are zeros
-    for (int v = 0; v < 4; ++v)
-      for (int r = rb0 * 16 + (int)threadIdx.x; r < rb1 * 16; r += kThreads)
-        store_device_coherent(partial + v * p.vec_stride + r, 0.0f);
-  }
-  finish_row_range<4>(p, lut, rs, rb0, rb1);
+  finish_row_range<4, (Q <= 4)>(p, lut, rs, rb0, rb1);
 }

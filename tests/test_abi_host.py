@@ -46,11 +46,11 @@ def test_size_helpers_follow_eq4():
     assert L.lutgemm_alpha_bytes(16, 64, 3, 24) == 0 and L.lutgemm_alpha_bytes(16, 64, 3, 12) == 0
     assert L.lutgemm_workspace_bytes(16, 64, 3, 64, mu=4) == 0
     assert L.lutgemm_workspace_bytes(16, 64, 3, 64, batch=33) == 0
-    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128) == 32768 + 524288 + 12 * 49152 * 4
-    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128, batch=4) == 32768 + 524288 + 4 * 12 * 4 * 49152 * 4
-    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128, batch=3) == 32768 + 524288 + 4 * 12 * 4 * 49152 * 4
-    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128, batch=2) == 32768 + 524288 + 2 * 12 * 2 * 49152 * 4
-    assert L.lutgemm_workspace_bytes(17, 1024, 3, 128) == 32768 + 524288 + 1 * 1 * 32 * 4       # 2 row blocks -> 32 rows
+    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128) == 32768 + 12 * 49152 * 4
+    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128, batch=4) == 32768 + 4 * 12 * 4 * 49152 * 4
+    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128, batch=3) == 32768 + 4 * 12 * 4 * 49152 * 4
+    assert L.lutgemm_workspace_bytes(49152, 12288, 3, 128, batch=2) == 32768 + 2 * 12 * 2 * 49152 * 4
+    assert L.lutgemm_workspace_bytes(17, 1024, 3, 128) == 32768 + 1 * 1 * 32 * 4       # 2 row blocks -> 32 rows
 
 
 @pytest.mark.parametrize("m,n,q,g,mode", [

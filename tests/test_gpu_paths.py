@@ -1,7 +1,8 @@
 """GPU parity for the kernel paths that only long rows reach: K groups of several tiles
 (a workgroup walks more than one table set and carries row sums from tile to tile) in the
 GEMV, pair and quad kernels, crossed with offsets, more than four planes, every scale
-mode and the shared-scale layout.  Every case first asks the library which grid it plans
+mode and the shared-scale layout; and row ranges longer than the running sums in LDS cover
+(pair and quad kernels).  Every case first asks the library which grid it plans
 (lutgemm_plan_grid) and asserts that the path meant is the path reached; all rows are then
 compared with the fp64 C oracle."""
 import numpy as np
@@ -97,6 +98,33 @@ def test_small_batch_several_tiles_per_k_group(m, n, q, g, mode, batch, width):
     assert tpg > 1, "this shape is meant to reach K groups of several (half, quarter) tiles"
     W = synth.weights_fp16(m, n, seed=12000 + m + q)
     X = synth.activations_fp16(n, seed=12500 + m + q, batch=batch)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    del W
+    _check_all_rows(p, X)
+
+
+# Row ranges longer than the running sums in LDS cover (240 row blocks for two vectors, 120
+# for four): the workgroup walks its range in stretches, each over all the (half, quarter)
+# tiles of its K group.  m, n, q, g, mode, batch, kernel width
+LONG_RANGE_CASES = [
+    (1000000, 72, 3, 8, "rtn", 2, 2),          # one half tile, two stretches
+    (1000000, 72, 3, 8, "rtn", 3, 4),          # one quarter, several stretches, three vectors
+    (130000, 1096, 3, 0, "greedy_z", 4, 4),    # two quarters per K group, one K group of quarters that do not exist
+    (65536, 16384, 2, 128, "greedy", 2, 2),    # two half tiles per K group, two stretches
+    (65536, 16384, 2, 128, "greedy", 4, 4),    # eight quarters per K group, two stretches
+]
+
+
+@pytest.mark.parametrize("m,n,q,g,mode,batch,width", LONG_RANGE_CASES)
+def test_small_batch_long_row_ranges(m, n, q, g, mode, batch, width):
+    kg, tpg, rs = L.lutgemm_plan_grid(m, n, q, g, width)
+    rb = (m + 15) // 16
+    blocks = -(-rb // rs) if width == 2 else 2 * -(-((rb + 1) // 2) // rs)
+    print(f"case long m={m} n={n} q={q} g={g} mode={mode} batch={batch}: width {width} grid KG={kg} TPG={tpg} RS={rs}, "
+          f"{blocks} row blocks per range", flush=True)
+    assert blocks > (240 if width == 2 else 120), "this shape is meant to reach row ranges of several stretches"
+    W = synth.weights_fp16(m, n, seed=13000 + n + q)
+    X = synth.activations_fp16(n, seed=13500 + n + q, batch=batch)
     p = Packed.from_weights(W, q, g, MODES[mode])
     del W
     _check_all_rows(p, X)
