@@ -1605,11 +1605,13 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
   if (m > (int64_t)1 << 30 || n > (int64_t)1 << 30) return LUTGEMM_EUNSUPPORTED;
   const bool shared = (flags & LUTGEMM_ALPHA_SHARED) != 0;
   if (shared && !z) return LUTGEMM_EINVAL;   // the shared-scale form always comes with offsets
-  // Measured on MI355X (q = 2..4, twelve layer shapes from 4096^2 to 49152 x 12288): the
-  // lookup path costs about a GEMV per four vectors, the matrix-core path the same for any
-  // batch up to 16; they cross between three and six vectors, earlier on small layers.
+  // Measured on MI355X (q = 3, thirteen layer shapes from 4096^2 to 49152 x 12288): the
+  // lookup path costs less than two GEMVs per four vectors, the matrix-core path the same
+  // for any batch up to 16; the lookup path wins up to four vectors (two on layers of at most
+  // 2^25 weights), the two tie at five and six on the layers of more than 2^28 weights, and
+  // the matrix cores win beyond.
   if ((flags & LUTGEMM_PATH_AUTO) != 0 && !shared && gg % 64 == 0 &&
-      (batch >= 5 || (batch >= 3 && m * n <= (int64_t)1 << 27)))
+      (batch >= 6 || (batch == 5 && m * n < (int64_t)1 << 28) || (batch >= 3 && m * n <= (int64_t)1 << 25)))
     return lutgemm_gemm_mfma(x, bits, alpha, z, y, q, g, mu, m, n, batch, flags & LUTGEMM_Y_F32, workspace,
                              workspace_bytes, hip_stream);
   const size_t need = lutgemm_workspace_bytes(m, n, q, g, mu, batch);
