@@ -194,6 +194,10 @@ def test_plan_grid_is_host_logic_and_covers_every_tile():
             assert kg >= 1 and tpg >= 1 and rs >= 1
             assert kg * tpg >= tiles > (kg - 1) * tpg
             assert rs <= 256 and (kg * rs <= 256 or rs == 1)
+    # the choices the kernels were measured with on a 256-unit device (FC1 of OPT-175B: one, two, four vectors)
+    assert L.lutgemm_plan_grid(49152, 12288, 3, 128, 1, 256) == (6, 2, 42)
+    assert L.lutgemm_plan_grid(49152, 12288, 3, 128, 2, 256) == (8, 3, 32)
+    assert L.lutgemm_plan_grid(49152, 12288, 3, 128, 4, 256) == (8, 6, 32)
     assert L.lutgemm_plan_grid(16, 262144, 3, 128, 1, 256)[1] > 1
     assert L.lutgemm_plan_grid(16, 262144, 5, 128, 1, 256)[1] > 1
     with pytest.raises(L.LutGemmError):
