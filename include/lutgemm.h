@@ -288,6 +288,10 @@ int lutgemm_gemm_dequant_mfma(const void* x, const void* bits, const void* alpha
               quarter tiles of 256 for vectors = 4),
      out[2]   row ranges (workgroups along the rows).
    Tests use it to show which code path a shape reaches; tuning scripts to explain a time.
+   The choice can be overridden for sweeps by environment variables read once per process
+   (LUTGEMM_TPG / LUTGEMM_RS for vectors = 1, LUTGEMM_PAIR_TPG / _RS, LUTGEMM_QUAD_TPG / _RS,
+   LUTGEMM_MFMA_TPG: tiles per K group, row ranges); results do not depend on the grid
+   beyond the order of the additions.
    LUTGEMM_EINVAL for malformed arguments, LUTGEMM_EHIP if the device cannot be asked.  */
 int lutgemm_plan_grid(int64_t m, int64_t n, int q, int g, int vectors, int compute_units, int* out);
 
