@@ -227,7 +227,7 @@ size_t lutgemm_group_workspace_bytes(const int64_t* m, const int64_t* n, int cou
    first call on a device looks the array's address up and enqueues a small kernel that
    zeroes its arrival counters.  LUTGEMM_EWORKSPACE if the layer needs more scratch than
    the array holds (lutgemm_workspace_bytes(m, n, q, g, mu, 1) > 8 MiB: beyond about 2^21
-   weights-rows x K-tiles; the OPT-175B layers need 0.8 to 2.9 MiB).  All calls on one GPU
+   weights-rows x K-tiles; the OPT-175B layers need 0.6 to 2.3 MiB).  All calls on one GPU
    share that GPU's array, which keeps the last call's partial sums: calls must be ordered
    on one stream (or otherwise not overlap); two that overlap race.  Same result, bit for
    bit, as lutgemm_gemv.                                                                 */
