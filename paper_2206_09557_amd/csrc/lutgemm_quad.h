@@ -113,7 +113,7 @@ __device__ __forceinline__ void quad_passes(const GemvParams& p, int64_t tile_ba
 // [32 * (b / 2), +32) of vector v for slot 16 * (b % 2) + sl, i.e. the 64 lanes of a store
 // write 64 consecutive floats (16 slots x 4 vectors of one key): no bank conflicts.  (A quad
 // launched for three vectors builds the fourth table set from the third vector.)  The
-// activations a lane needs for that: 8 halfs, fetched ahead of the quarter before.
+// activations a lane needs for that: 8 halfs, fetched a quarter ahead.
 __device__ __forceinline__ u32x4 quad_fetch_x(const GemvParams& p, int id, int wave, int lane) {
   const int kt = id >> 2, t0 = (id >> 1) & 1, h = id & 1;
   const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
@@ -132,137 +132,190 @@ __device__ __forceinline__ bool quarter_exists(const GemvParams& p, int id) {
   return t0 < T && 32 * h * T + t0 < chunks;
 }
 
-// One workgroup, one quarter (kt, t0, h), row blocks [rb0, rb1) with rb0 even.  xraw: what
-// quad_fetch_x returned for this quarter.
-template <int Q, int AMODE, bool HAS_Z, int kDepth>
-__device__ __forceinline__ void quad_tile_body(const GemvParams& p, float* lut, int kt, int t0, int h, int rb0, int rb1,
-                                               bool first_tile, const u32x4& xraw) {
-  using U = Unit<Q, 0, Q, 1, AMODE, HAS_Z>;
-  int lane = threadIdx.x & 63;
-  asm volatile("" : "+v"(lane));   // see tile_body
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int chunks_in_tile = min(128, p.nchunks - 128 * kt);
-  const int tile_T = chunks_in_tile > 64 ? 2 : 1;
-  const int64_t tile_base = (int64_t)kt * p.RB * Q * 2048;
-  const int half = lane >> 5;                 // which row block of the pair this lane works on
-  const int lq = lane & 31;                   // lane within the half = slot it builds / position in the quarter
-  const int slab_lane = 32 * h + lq;          // lane position inside the 1 KB slabs
-  const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
+__device__ __forceinline__ int next_quarter(const GemvParams& p, int id, int id_end) {
+  while (id < id_end && !quarter_exists(p, id)) ++id;
+  return id;
+}
 
+// What a wavefront prepares for a quarter while the slower wavefronts of the workgroup are
+// still busy with the quarter before (it would otherwise only wait for them at the barrier
+// that frees the tables): the 32 table entries it will store, the groups of its dwords, and
+// the fetch of its first unit.  After the barrier the entries are stored, a second barrier
+// says that the tables stand, and the lookups start on a unit that has arrived meanwhile.
+template <int Q, int AMODE, bool HAS_Z, bool AHEAD>
+struct QuadQuarter {
+  // planes fetched together: all up to four; beyond that half of them, or two where every
+  // dword has a scale set of its own (16 accumulators leave fewer registers than in the
+  // other kernels: three of eight planes even with quad-shared scales)
+  static constexpr int PP = (AMODE & 3) == kAlphaQuad ? (Q > 4 ? (Q > 7 ? 3 : (Q + 1) / 2) : Q)
+                                                      : ((Q > 4 || (Q >= 3 && HAS_Z)) ? 2 : Q);
+  // AHEAD (the kernel's every tile has quad-shared scales): the first unit's fetch is part
+  // of the preparation where a unit is fetched in one piece (a scale set per dword leaves no
+  // registers for it)
+  static constexpr bool kFirstUnit = AHEAD && PP == Q && (AMODE & 3) == kAlphaQuad;
+  // ... and likewise the table entries and the next quarter's activations are only held
+  // across the lookups and the barrier with quad-shared scales
+  static constexpr bool kAheadTables = AHEAD && (AMODE & 3) == kAlphaQuad;
+  int kt, t0, h, tile_T;
+  int64_t tile_base;
   int grp[4][1];
+  float entries[32];
+  Unit<Q, 0, Q, 1, AMODE, HAS_Z> u;   // the wavefront's first unit (kFirstUnit)
+};
+
+template <int Q, int AMODE, bool HAS_Z, bool AHEAD>
+__device__ __forceinline__ void quad_entries(QuadQuarter<Q, AMODE, HAS_Z, AHEAD>& qq, const GemvParams& p, int wave, int lane,
+                                             const u32x4& xraw) {
+  const int chunks_in_tile = min(128, p.nchunks - 128 * qq.kt);
+  float xs[8];
+  unpack_x(xraw, qq.tile_T * (32 * qq.h + 16 * (wave & 1) + (lane >> 2)) + qq.t0 < chunks_in_tile, xs);
+#pragma unroll
+  for (int hi = 0; hi < 2; ++hi) {
+    float e[16];
+    table_entries16(wave >> 1, hi, xs, e);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) qq.entries[hi * 16 + k] = e[k];
+  }
+}
+
+// rb0: first row block of the stretch (even), n_units: its pairs of row blocks.
+template <int Q, int AMODE, bool HAS_Z, bool AHEAD>
+__device__ __forceinline__ void quad_prepare(QuadQuarter<Q, AMODE, HAS_Z, AHEAD>& qq, const GemvParams& p, int id, int rb0,
+                                             int n_units, int wave, int lane, const u32x4& xraw, bool with_entries) {
+  qq.kt = id >> 2;
+  qq.t0 = (id >> 1) & 1;
+  qq.h = id & 1;
+  const int chunks_in_tile = min(128, p.nchunks - 128 * qq.kt);
+  qq.tile_T = chunks_in_tile > 64 ? 2 : 1;
+  qq.tile_base = (int64_t)qq.kt * p.RB * Q * 2048;
+  const int half = lane >> 5, lq = lane & 31;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const int L = (lq & ~3) | ((s + lq) & 3);
-    grp[s][0] = group_of_chunk(p, 128 * kt + min(tile_T * (32 * h + L) + t0, chunks_in_tile - 1));
+    qq.grp[s][0] = group_of_chunk(p, 128 * qq.kt + min(qq.tile_T * (32 * qq.h + L) + qq.t0, chunks_in_tile - 1));
   }
+  if constexpr (QuadQuarter<Q, AMODE, HAS_Z, AHEAD>::kFirstUnit) {
+    // (unconditional: a wavefront without a unit fetches the last one and does not use it)
+    const int rb = min(rb0 + 2 * min(wave, n_units - 1) + half, p.RB - 1);
+    load_unit<true>(qq.u, p, qq.tile_base, rb, 32 * qq.h + lq, qq.grp, nullptr, 0, false, qq.tile_T, qq.t0);
+  }
+  if (with_entries) quad_entries(qq, p, wave, lane, xraw);
+}
 
-  // planes fetched together: all up to four; beyond that half of them, or two where every
-  // dword has a scale set of its own (16 accumulators leave fewer registers than in the
-  // other kernels); a second unit in flight only with quad-shared scales
-  constexpr int PP = (AMODE & 3) == kAlphaQuad ? (Q > 4 ? (Q > 7 ? 3 : (Q + 1) / 2) : Q)
-                                               : ((Q > 4 || (Q == 4 && HAS_Z)) ? 2 : Q);
-  constexpr int kScaleRegs = (AMODE & kAlphaShared) ? 2 : 2 * Q;
-  constexpr int kFit = (PP < Q || (AMODE & 3) != kAlphaQuad || 4 * Q + kScaleRegs + (HAS_Z ? 2 : 0) > 24) ? 0 : 1;
-  constexpr int D = kFit < kDepth ? kFit : kDepth;
+// One workgroup, the quarters [id, id_end) that exist (all of tiles with the same number of
+// sub-slabs, hence one scale mode AMODE), row blocks [rb0, rb1) with rb0 even: a stretch of
+// the workgroup's row range whose running sums fit LDS.  `first`: no quarter of the K group
+// has been added to the running sums of this stretch yet (in and out); `fresh`: nothing in
+// LDS is in use by other wavefronts when the call starts.
+template <int Q, int AMODE, bool HAS_Z, bool AHEAD>
+__device__ __forceinline__ void quad_quarters(const GemvParams& p, float* lut, int id, int id_end, int rb0, int rb1,
+                                              bool& first, bool fresh) {
+  using QQ = QuadQuarter<Q, AMODE, HAS_Z, AHEAD>;
+  constexpr int PP = QQ::PP;
+  id = next_quarter(p, id, id_end);
+  if (id >= id_end) return;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n_units = (rb1 - rb0 + 1) >> 1;   // pairs of row blocks
-  const int u_clamp = n_units - 1;
   const int rb_last = p.RB - 1;               // a pair's second block may lie past the end: fetch the last one instead
-  U u[D + 1];
-  int uid[D + 1];
-  if (PP == Q && threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = (D > 0 ? D : 1) * kWaves;
-#pragma unroll
-  for (int k = 0; k <= D; ++k) uid[k] = wave + k * kWaves;
-  if (PP == Q) {
-#pragma unroll
-    for (int k = 0; k < D; ++k) {
-      const int rb = min(rb0 + 2 * min(uid[k], u_clamp) + half, rb_last);
-      load_unit<true>(u[k], p, tile_base, rb, slab_lane, grp, nullptr, out_row, false, tile_T, t0);
-    }
-  }
 
-  // ---- tables ----
-  {
-    const int kh = wave >> 1;
-    float xs[8];
-    unpack_x(xraw, tile_T * (32 * h + 16 * (wave & 1) + (lane >> 2)) + t0 < chunks_in_tile, xs);
-    float* dst = lut + ((wave & 1) << 14) + lane;
+  QQ qq;
+  quad_prepare(qq, p, id, rb0, n_units, wave, (int)(threadIdx.x & 63), quad_fetch_x(p, id, wave, threadIdx.x & 63),
+               QQ::kAheadTables);
+  for (;;) {
+    const int next = next_quarter(p, id + 1, id_end);
+    // Everything derived from the lane id below belongs to this quarter only: the empty asm
+    // stops the optimiser from keeping it in registers from quarter to quarter.
+    int lane = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane));
+    const int half = lane >> 5;                 // which row block of the pair this lane works on
+    const int lq = lane & 31;                   // position in the quarter
+    const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
+    // Running sums in LDS, [row block of the stretch][vector][16 rows].  After the reduction
+    // both 16-lane groups of a half hold the results of the half's row block for all four
+    // vectors: group 0 adds vectors 0 and 2, group 1 vectors 1 and 3.  (A pair's second block
+    // may be the padded one past the range: it has a place in LDS and is never copied out.)
+    const int odd = (lane >> 4) & 1;
+    float* const run_lane = lut + kRunWord + (half * 4 + odd) * 16 + out_row;
+    // every lookup of the quarter before is done before its tables are overwritten (and the
+    // stretch before has been copied out before its sums are)
+    if (!first || !fresh) __syncthreads();
+    if (!QQ::kAheadTables) quad_entries(qq, p, wave, lane, quad_fetch_x(p, id, wave, lane));
+    {
+      float* dst = lut + ((wave & 1) << 14) + lane;
 #pragma unroll
-    for (int hi = 0; hi < 2; ++hi) {
-      float e[16];
-      table_entries16(kh, hi, xs, e);
-#pragma unroll
-      for (int k = 0; k < 16; ++k) dst[(kh * 32 + hi * 16 + k) << 6] = e[k];
+      for (int k = 0; k < 32; ++k) dst[((wave >> 1) * 32 + k) << 6] = qq.entries[k];
     }
-  }
-  __syncthreads();
+    if (PP == Q && threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = kWaves;   // units 0..kWaves-1 are taken
+    // the activations of the quarter after this one, on their way during the lookups
+    u32x4 xnext = {0u, 0u, 0u, 0u};
+    if (QQ::kAheadTables) xnext = quad_fetch_x(p, next < id_end ? next : id, wave, lane);
+    __syncthreads();   // the tables stand
 
-  uint32_t lane_base[4];
-  f32x4v sum_x[4];
+    uint32_t lane_base[4];
+    f32x4v sum_x[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const uint32_t L = ((uint32_t)lq & ~3u) | ((uint32_t)(s + lq) & 3u);
-    lane_base[s] = ((L & 15u) << 4) | ((L >> 4) << 8);
-    sum_x[s] = HAS_Z ? lds_f32x4(((L >> 4) << 16) | (0xffu << 8) | ((L & 15u) << 4)) : f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
-  }
-  // one offset per quad of slots: only the sum over the four slots is needed
-  if (HAS_Z && (AMODE & 3) == kAlphaQuad) sum_x[0] = (sum_x[0] + sum_x[1]) + (sum_x[2] + sum_x[3]);
-
-  // Running sums in LDS, [row block of the range][vector][16 rows].  After the reduction
-  // both 16-lane groups of a half hold the results of the half's row block for all four
-  // vectors: group 0 adds vectors 0 and 2, group 1 vectors 1 and 3.  (A pair's second block
-  // may be the padded one past the range: it has a place in LDS and is never copied out.)
-  const int odd = (lane >> 4) & 1;
-  float* const run_lane = lut + kRunWord + (half * 4 + odd) * 16 + out_row;
-  if constexpr (PP < Q) {
-    for (int un = wave; un < n_units; un += kWaves) {
-      const int rb = min(rb0 + 2 * un + half, rb_last);
-      float acc[4][4];
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[v][r] = 0.0f;
-      quad_passes<Q, 0, PP, AMODE, HAS_Z>(p, tile_base, rb, slab_lane, grp, nullptr, out_row, tile_T, t0, lane_base, sum_x,
-                                          acc);
-      float sv[4];
-#pragma unroll
-      for (int v = 0; v < 4; ++v) sv[v] = half_rows_reduce(acc[v], lane);
-      float* r = run_lane + un * 128;
-      const float lo = odd ? sv[1] : sv[0], hi = odd ? sv[3] : sv[2];
-      r[0] = first_tile ? lo : r[0] + lo;
-      r[32] = first_tile ? hi : r[32] + hi;
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t L = ((uint32_t)lq & ~3u) | ((uint32_t)(s + lq) & 3u);
+      lane_base[s] = ((L & 15u) << 4) | ((L >> 4) << 8);
+      sum_x[s] = HAS_Z ? lds_f32x4(((L >> 4) << 16) | (0xffu << 8) | ((L & 15u) << 4)) : f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
     }
-  } else {
-    // The pair kernel's loop: dynamic unit queue, D units fetched ahead, one exit at the bottom.
-    if (uid[0] >= n_units) return;
-    do {
+    // one offset per quad of slots: only the sum over the four slots is needed
+    if (HAS_Z && (AMODE & 3) == kAlphaQuad) sum_x[0] = (sum_x[0] + sum_x[1]) + (sum_x[2] + sum_x[3]);
+
+    const int slab_lane = 32 * qq.h + lq;      // lane position inside the 1 KB slabs
+    if constexpr (PP < Q) {
+      for (int un = wave; un < n_units; un += kWaves) {
+        const int rb = min(rb0 + 2 * un + half, rb_last);
+        float acc[4][4];
 #pragma unroll
-      for (int j = 0; j <= D; ++j) {
-        constexpr int kRing = D + 1;
-        const int fill = (j + D) % kRing;
-        if (D > 0) uid[fill] = next_unit(lut, lane);
-        {
-          const int rb = min(rb0 + 2 * min(uid[fill], u_clamp) + half, rb_last);
-          load_unit<true>(u[fill], p, tile_base, rb, slab_lane, grp, nullptr, out_row, false, tile_T, t0);
-        }
-        __builtin_amdgcn_sched_barrier(0);   // the fetch stays ahead of the lookups below
-        if (uid[j] < n_units) {
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[v][r] = 0.0f;
+        quad_passes<Q, 0, PP, AMODE, HAS_Z>(p, qq.tile_base, rb, slab_lane, qq.grp, nullptr, out_row, qq.tile_T, qq.t0,
+                                            lane_base, sum_x, acc);
+        float sv[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sv[v] = half_rows_reduce(acc[v], lane);
+        float* r = run_lane + un * 128;
+        const float lo = odd ? sv[1] : sv[0], hi = odd ? sv[3] : sv[2];
+        r[0] = first ? lo : r[0] + lo;
+        r[32] = first ? hi : r[32] + hi;
+      }
+    } else {
+      // Dynamic unit queue (see tile_body): a wavefront starts with unit `wave`, whose fetch
+      // quad_prepare has issued, and takes every further one from the queue; nothing is
+      // fetched ahead of the unit being computed.
+      int cur = wave;
+      if (cur < n_units) {
+        for (;;) {
+          if (!QQ::kFirstUnit)
+            load_unit<true>(qq.u, p, qq.tile_base, min(rb0 + 2 * cur + half, rb_last), slab_lane, qq.grp, nullptr, 0, false,
+                            qq.tile_T, qq.t0);
           float acc[4][4];
 #pragma unroll
           for (int v = 0; v < 4; ++v)
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[v][r] = 0.0f;
-          accumulate_quad(u[j], lane_base, sum_x, acc);
+          accumulate_quad(qq.u, lane_base, sum_x, acc);
           float sv[4];
 #pragma unroll
           for (int v = 0; v < 4; ++v) sv[v] = half_rows_reduce(acc[v], lane);
-          float* r = run_lane + uid[j] * 128;
+          float* r = run_lane + cur * 128;
           const float lo = odd ? sv[1] : sv[0], hi = odd ? sv[3] : sv[2];
-          r[0] = first_tile ? lo : r[0] + lo;
-          r[32] = first_tile ? hi : r[32] + hi;
+          r[0] = first ? lo : r[0] + lo;
+          r[32] = first ? hi : r[32] + hi;
+          cur = next_unit(lut, lane);
+          if (cur >= n_units) break;
+          if (QQ::kFirstUnit)
+            load_unit<true>(qq.u, p, qq.tile_base, min(rb0 + 2 * cur + half, rb_last), slab_lane, qq.grp, nullptr, 0, false,
+                            qq.tile_T, qq.t0);
         }
-        if (D == 0) uid[0] = next_unit(lut, lane);
       }
-    } while (uid[0] < n_units);
+    }
+    first = false;
+    if (next >= id_end) break;
+    quad_prepare(qq, p, next, rb0, n_units, wave, lane, xnext, QQ::kAheadTables);   // in the shadow of the slower wavefronts
+    id = next;
   }
 }
 
@@ -279,35 +332,19 @@ __global__ __launch_bounds__(kThreads) void lutgemm_quad_kernel(GemvParams p) {
   const int rb0 = 2 * pair0;
   const int rb1 = min(2 * pair1, p.RB);
   float* partial = p.partial + (int64_t)kg * p.kg_stride;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
+  // the K group's quarters: those of tiles with two sub-slabs, then those of a last tile with one
+  const int id0 = kg * p.TPG, id1 = min(id0 + p.TPG, p.NT);
+  const int last_tile = (p.nchunks - 1) >> 7;
+  const int split = (p.nchunks - 128 * last_tile > 64) ? id1 : max(id0, min(id1, 4 * last_tile));
   constexpr int kStretch = kRunBlocks / 4;   // even
+  // (the preparation ahead of the barrier needs registers that only the kernels have whose
+  // scale mode is the quad-shared one for every tile)
+  constexpr bool kAhead = (AM2 & 3) == kAlphaQuad && (AM1 & 3) == kAlphaQuad;
   for (int s0 = rb0; s0 < rb1; s0 += kStretch) {
     const int s1 = min(s0 + kStretch, rb1);
-    // The quarters of the K group that exist, one after the other; the activations of the
-    // next one are fetched before the lookups of the current one start.
-    const int id_end = min((kg + 1) * p.TPG, p.NT);
-    int id = kg * p.TPG;
-    while (id < id_end && !quarter_exists(p, id)) ++id;
     bool first = true;
-    u32x4 xraw = {0u, 0u, 0u, 0u};
-    if (id < id_end) xraw = quad_fetch_x(p, id, wave, lane);
-    while (id < id_end) {
-      int next = id + 1;
-      while (next < id_end && !quarter_exists(p, next)) ++next;
-      // every lookup of the quarter before is done before its tables are overwritten (and
-      // the stretch before has been copied out before its sums are)
-      if (!first || s0 > rb0) __syncthreads();
-      const u32x4 xnext = quad_fetch_x(p, next < id_end ? next : id, wave, lane);
-      const int kt = id >> 2, t0 = (id >> 1) & 1, h = id & 1;
-      if (min(128, p.nchunks - 128 * kt) > 64)
-        quad_tile_body<Q, AM2, HAS_Z, kPairDepth>(p, lut, kt, t0, h, s0, s1, first, xraw);
-      else
-        quad_tile_body<Q, AM1, HAS_Z, kPairDepth>(p, lut, kt, t0, h, s0, s1, first, xraw);
-      xraw = xnext;
-      id = next;
-      first = false;
-    }
+    quad_quarters<Q, AM2, HAS_Z, kAhead>(p, lut, id0, split, s0, s1, first, s0 == rb0);
+    quad_quarters<Q, AM1, HAS_Z, kAhead>(p, lut, split, id1, s0, s1, first, s0 == rb0);
     if (first) {   // a K group made of non-existent quarters only: its sums are zeros
       if (s0 > rb0) __syncthreads();
       for (int i = threadIdx.x; i < (s1 - s0) * 64; i += kThreads) lut[kRunWord + i] = 0.0f;
