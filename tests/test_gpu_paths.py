@@ -103,6 +103,31 @@ def test_small_batch_several_tiles_per_k_group(m, n, q, g, mode, batch, width):
     _check_all_rows(p, X)
 
 
+# K groups that run from tiles of two sub-slabs into a last tile of one (the two kinds of
+# tile are walked by different instantiations of the same code, one after the other, on
+# the same running sums).  m, n, q, g, mode, batch, kernel width
+MIXED_TILE_CASES = [
+    (640, 20736, 3, 128, "greedy_z", 4, 4),    # 20 tiles + 256 columns; three quarters per K group
+    (2000, 44288, 3, 128, "greedy", 2, 2),     # 43 tiles + 256 columns; three half tiles per K group
+]
+
+
+@pytest.mark.parametrize("m,n,q,g,mode,batch,width", MIXED_TILE_CASES)
+def test_small_batch_k_group_across_tile_kinds(m, n, q, g, mode, batch, width):
+    kg, tpg, rs = L.lutgemm_plan_grid(m, n, q, g, width)
+    tiles = (n // 8 + 127) // 128
+    assert 0 < n // 8 - 128 * (tiles - 1) <= 64, "the last tile is meant to have one sub-slab"
+    first_of_last_tile = (tiles - 1) * width
+    print(f"case mixed m={m} n={n} q={q} g={g} mode={mode} batch={batch}: width {width} grid KG={kg} TPG={tpg} RS={rs}",
+          flush=True)
+    assert first_of_last_tile % tpg != 0, "a K group is meant to start before the last tile and end in it"
+    W = synth.weights_fp16(m, n, seed=14000 + n + q)
+    X = synth.activations_fp16(n, seed=14500 + n + q, batch=batch)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    del W
+    _check_all_rows(p, X)
+
+
 # Row ranges longer than the running sums in LDS cover (240 row blocks for two vectors, 120
 # for four): the workgroup walks its range in stretches, each over all the (half, quarter)
 # tiles of its K group.  m, n, q, g, mode, batch, kernel width
