@@ -333,7 +333,6 @@ __device__ __forceinline__ float compute_unit(const Unit<Q, 0, Q, T, AMODE, HAS_
 // lane L of the building wavefront owns the table of chunk T * L + t.  The activations of a
 // slot are fetched first (fetch_slot_x) so that their latency overlaps whatever is issued in
 // between; the caller ends the build with the workgroup barrier that publishes the tables.
-constexpr int kBuildPasses = 1;   // table slots per wavefront in the pair and quad kernels (16 slots, 16 wavefronts)
 
 template <int T>
 __device__ __forceinline__ u32x4 fetch_slot_x(const GemvParams& p, int kt, int chunks_in_tile, int slot, int lane) {
@@ -780,7 +779,7 @@ __global__ __launch_bounds__(kThreads) void lutgemm_gemv_group_kernel(GroupParam
 // a unit is (half tile, row block).
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kPairDepth = 1;   // units fetched ahead in the pair and quad kernels, where the registers allow
+constexpr int kPairDepth = 1;   // units fetched ahead in the pair kernel, where the registers allow
 
 __device__ __forceinline__ f32x2 lds_f32x2(uint32_t byte_addr) {
   return *(const __attribute__((address_space(3))) f32x2*)(uintptr_t)byte_addr;
@@ -945,20 +944,16 @@ __device__ __forceinline__ void pair_tile_body(const GemvParams& p, float* lut, 
     unpack_x(xraw0, my_chunk < chunks_in_tile, xa);
     unpack_x(xraw1, my_chunk < chunks_in_tile, xb);
     f32x2* dst = reinterpret_cast<f32x2*>(lut) + ((lane >> 5) << 13) + (lane & 31);
+    const int kh = wave & 7, hi = wave >> 3;   // 16 slots, 16 wavefronts
+    float ea[16], eb[16];
+    table_entries16(kh, hi, xa, ea);
+    table_entries16(kh, hi, xb, eb);
 #pragma unroll
-    for (int b = 0; b < kBuildPasses; ++b) {
-      const int slot = wave + b * kWaves;
-      const int kh = slot & 7, hi = slot >> 3;
-      float ea[16], eb[16];
-      table_entries16(kh, hi, xa, ea);
-      table_entries16(kh, hi, xb, eb);
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        f32x2 e;
-        e.x = ea[k];
-        e.y = eb[k];
-        dst[(kh * 32 + hi * 16 + k) << 5] = e;
-      }
+    for (int k = 0; k < 16; ++k) {
+      f32x2 e;
+      e.x = ea[k];
+      e.y = eb[k];
+      dst[(kh * 32 + hi * 16 + k) << 5] = e;
     }
   }
   __syncthreads();

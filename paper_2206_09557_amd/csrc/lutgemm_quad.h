@@ -13,7 +13,8 @@
 // A quarter uses 32 of the 64 lanes' worth of a 1 KB slab, so a wavefront works on TWO row
 // blocks at once: lanes 0..31 on row block 2u, lanes 32..63 on row block 2u + 1, both on the
 // same 32 slots.  A unit is (quarter, pair of row blocks).  K is split over quarters
-// (id = 4 * tile + 2 * sub-slab + half); split-K partials and the final reduction are those
+// (id = 4 * tile + 2 * sub-slab + half); the sums over the quarters of a K group stand in
+// LDS (as in the GEMV and pair kernels), split-K partials and the final reduction are those
 // of the GEMV kernel, for four vectors.
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
