@@ -328,6 +328,45 @@ def test_random_shapes_all_paths(m, n, q, g, mode, batch):
         np.testing.assert_array_equal(run(p, x, f32_out=True, shared=True), y)
 
 
+def _random_wide_cases(count, seed):
+    """Long rows, few of them, small batches: K groups of several (half, quarter) tiles in the
+    pair and quad kernels, ragged last tiles of either kind, every scale mode."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        q = int(rng.integers(1, 9))
+        g_units = int(rng.choice([1, 2, 3, 4, 8, 16, 24]))
+        groups = int(rng.integers(40, 1200))
+        n = 8 * g_units * groups
+        if n < 6144 or n > 70000:
+            continue
+        g = 0 if rng.random() < 0.15 else 8 * g_units
+        m = int(rng.integers(1, 600))
+        mode = ["greedy", "greedy_z", "rtn"][int(rng.integers(0, 3))]
+        batch = [2, 3, 4, 6, 7][int(rng.integers(0, 5))]
+        cases.append((m, n, q, g, mode, batch))
+    return cases
+
+
+@pytest.mark.parametrize("m,n,q,g,mode,batch", _random_wide_cases(24, 20240611))
+def test_random_wide_shapes_small_batch(m, n, q, g, mode, batch):
+    grids = [L.lutgemm_plan_grid(m, n, q, g, width) for width in (1, 2, 4)]
+    print(f"case wide m={m} n={n} q={q} g={g} mode={mode} batch={batch} grids (KG, TPG, RS) {grids}", flush=True)
+    W = synth.weights_fp16(m, n, seed=9000 + m + 3 * n + q)
+    X = synth.activations_fp16(n, seed=9500 + m + n, batch=batch)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    del W
+    bound = _bound(p)
+    y_ref, _ = c_oracle.gemv_packed(p.bits, p.alpha, p.z, X, p.m, p.n, p.q, p.g)
+    y = run(p, X, f32_out=True)
+    for b in range(batch):
+        check_parity(y[b], y_ref[b], X[b], bound, f32_out=True)
+    np.testing.assert_array_equal(run(p, X, f32_out=True), y)    # bitwise reproducible
+    if mode == "rtn":                      # shared-scale layout: bitwise the same as per-plane scales
+        p.share()
+        np.testing.assert_array_equal(run(p, X, f32_out=True, shared=True), y)
+
+
 @pytest.mark.parametrize("m,n,q,g,batch", [
     (16, 262144, 2, 128, None),     # one row block, 256 K tiles: deep split-K
     (40, 65536, 3, 1024, 4),        # few rows, long rows, four vectors
