@@ -88,6 +88,30 @@ __device__ __forceinline__ float dpp_f32(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
 
+// Lane exchanges of the row reductions, in registers (no trip through the LDS crossbar,
+// whose latency every unit of a wavefront would wait for three or four times in a row).
+// lane i <- lane i ^ 4: two DPP moves within the row of 16, one per direction, each written
+// into the two banks of four lanes it is right for.
+__device__ __forceinline__ float lane_xor4(float v) {
+  const unsigned x = __builtin_bit_cast(unsigned, v);
+  unsigned t = __builtin_amdgcn_update_dpp(x, x, 0x104 /* row_shl:4 */, 0xf, 0x5, false);   // banks 0, 2: lane i + 4
+  t = __builtin_amdgcn_update_dpp(t, x, 0x114 /* row_shr:4 */, 0xf, 0xa, false);            // banks 1, 3: lane i - 4
+  return __builtin_bit_cast(float, t);
+}
+// s + (s of lane i ^ 16), s + (s of lane i ^ 32): the swap instructions exchange the odd rows
+// of 16 (the upper 32 lanes) of one operand with the even rows (the lower 32) of the other;
+// with both operands s, the two results are s and its partner, in one order or the other.
+__device__ __forceinline__ float sum_lane_xor16(float s) {
+  const unsigned x = __builtin_bit_cast(unsigned, s);
+  const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+}
+__device__ __forceinline__ float sum_lane_xor32(float s) {
+  const unsigned x = __builtin_bit_cast(unsigned, s);
+  const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+}
+
 __device__ __forceinline__ float lds_f32(uint32_t byte_addr) {
   // The table array is the only LDS object of the kernel and starts at LDS address 0.
   return *(const __attribute__((address_space(3))) float*)(uintptr_t)byte_addr;
@@ -148,12 +172,12 @@ __device__ __forceinline__ float quad_rows_reduce(const float (&acc)[4], int lan
   const bool b2 = lane & 4, b3 = lane & 8;
   const float keep0 = b2 ? acc[2] : acc[0], send0 = b2 ? acc[0] : acc[2];
   const float keep1 = b2 ? acc[3] : acc[1], send1 = b2 ? acc[1] : acc[3];
-  const float h0 = keep0 + __shfl_xor(send0, 4);
-  const float h1 = keep1 + __shfl_xor(send1, 4);
+  const float h0 = keep0 + lane_xor4(send0);
+  const float h1 = keep1 + lane_xor4(send1);
   const float keep = b3 ? h1 : h0, send = b3 ? h0 : h1;
   float s = keep + dpp_f32<kDppRowRor8>(send);
-  s += __shfl_xor(s, 16);
-  s += __shfl_xor(s, 32);
+  s = sum_lane_xor16(s);
+  s = sum_lane_xor32(s);
   *row_in_block = 4 * (lane & 3) + (b2 ? 2 : 0) + (b3 ? 1 : 0);
   return s;
 }
