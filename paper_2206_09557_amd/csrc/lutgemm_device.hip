@@ -90,13 +90,24 @@ __device__ __forceinline__ float dpp_f32(float v) {
 
 // Lane exchanges of the row reductions, in registers (no trip through the LDS crossbar,
 // whose latency every unit of a wavefront would wait for three or four times in a row).
-// lane i <- lane i ^ 4: two DPP moves within the row of 16, one per direction, each written
-// into the two banks of four lanes it is right for.
-__device__ __forceinline__ float lane_xor4(float v) {
-  const unsigned x = __builtin_bit_cast(unsigned, v);
-  unsigned t = __builtin_amdgcn_update_dpp(x, x, 0x104 /* row_shl:4 */, 0xf, 0x5, false);   // banks 0, 2: lane i + 4
-  t = __builtin_amdgcn_update_dpp(t, x, 0x114 /* row_shr:4 */, 0xf, 0xa, false);            // banks 1, 3: lane i - 4
-  return __builtin_bit_cast(float, t);
+// The two halving steps of the row reductions.  The partner's value comes through DPP moves
+// written into the banks of four lanes each is right for (the compiler folds them into the
+// additions where it can, and it is the compiler that keeps the wait states a DPP read needs
+// after the write of its source: hand-written DPP instructions in inline assembly would not get
+// them and have returned stale values here):
+//   lanes with bit 2 clear: a0[i] + a0[i + 4],  lanes with bit 2 set: a2[i] + a2[i - 4];
+//   lanes with bit 3 clear: h0[i] + h0[i + 8],  lanes with bit 3 set: h1[i] + h1[i - 8].
+__device__ __forceinline__ float halve_over_lane_bit2(float a0, float a2, bool bit2) {
+  const unsigned x0 = __builtin_bit_cast(unsigned, a0), x2 = __builtin_bit_cast(unsigned, a2);
+  unsigned t = __builtin_amdgcn_update_dpp(x2, x0, 0x104 /* row_shl:4 */, 0xf, 0x5, false);   // banks 0, 2: a0 of lane i + 4
+  t = __builtin_amdgcn_update_dpp(t, x2, 0x114 /* row_shr:4 */, 0xf, 0xa, false);             // banks 1, 3: a2 of lane i - 4
+  return (bit2 ? a2 : a0) + __builtin_bit_cast(float, t);
+}
+__device__ __forceinline__ float halve_over_lane_bit3(float h0, float h1, bool bit3) {
+  const unsigned x0 = __builtin_bit_cast(unsigned, h0), x1 = __builtin_bit_cast(unsigned, h1);
+  unsigned t = __builtin_amdgcn_update_dpp(x1, x0, 0x128 /* row_ror:8 */, 0xf, 0x3, false);   // lanes 0..7 of a row: h0 of lane i + 8
+  t = __builtin_amdgcn_update_dpp(t, x1, 0x128, 0xf, 0xc, false);                              // lanes 8..15: h1 of lane i - 8
+  return (bit3 ? h1 : h0) + __builtin_bit_cast(float, t);
 }
 // s + (s of lane i ^ 16), s + (s of lane i ^ 32): the swap instructions exchange the odd rows
 // of 16 (the upper 32 lanes) of one operand with the even rows (the lower 32) of the other;
@@ -170,12 +181,9 @@ constexpr int kDppRowRor8 = 0x128;       // lane i <- lane (i + 8) mod 16 within
 // Halving exchange over lane bits 2 and 3, then a plain sum over lane bits 4 and 5.
 __device__ __forceinline__ float quad_rows_reduce(const float (&acc)[4], int lane, int* row_in_block) {
   const bool b2 = lane & 4, b3 = lane & 8;
-  const float keep0 = b2 ? acc[2] : acc[0], send0 = b2 ? acc[0] : acc[2];
-  const float keep1 = b2 ? acc[3] : acc[1], send1 = b2 ? acc[1] : acc[3];
-  const float h0 = keep0 + lane_xor4(send0);
-  const float h1 = keep1 + lane_xor4(send1);
-  const float keep = b3 ? h1 : h0, send = b3 ? h0 : h1;
-  float s = keep + dpp_f32<kDppRowRor8>(send);
+  const float h0 = halve_over_lane_bit2(acc[0], acc[2], b2);   // rows 0 or 2 of the lane's four
+  const float h1 = halve_over_lane_bit2(acc[1], acc[3], b2);   // rows 1 or 3
+  float s = halve_over_lane_bit3(h0, h1, b3);
   s = sum_lane_xor16(s);
   s = sum_lane_xor32(s);
   *row_in_block = 4 * (lane & 3) + (b2 ? 2 : 0) + (b3 ? 1 : 0);

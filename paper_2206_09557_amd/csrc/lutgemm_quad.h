@@ -25,18 +25,23 @@ __device__ __forceinline__ f32x4v lds_f32x4(uint32_t byte_addr) {
 
 // quad_rows_reduce for a 32-lane half: four per-lane values (rows 4k..4k+3, k = lane % 4) ->
 // every lane holds the sum over the 8 quads of its half for ONE of its rows.
-// IN_REGISTERS: the exchanges stay in registers (see lane_xor4); the kernels that are short
+// IN_REGISTERS: the exchanges stay in registers (see halve_over_lane_bit2); the kernels that are short
 // of registers (several fetches per unit) send them through the LDS crossbar instead.
 template <bool IN_REGISTERS = true>
 __device__ __forceinline__ float half_rows_reduce(const float (&acc)[4], int lane) {
   const bool b2 = lane & 4, b3 = lane & 8;
+  if (IN_REGISTERS) {
+    const float h0 = halve_over_lane_bit2(acc[0], acc[2], b2);
+    const float h1 = halve_over_lane_bit2(acc[1], acc[3], b2);
+    return sum_lane_xor16(halve_over_lane_bit3(h0, h1, b3));
+  }
   const float keep0 = b2 ? acc[2] : acc[0], send0 = b2 ? acc[0] : acc[2];
   const float keep1 = b2 ? acc[3] : acc[1], send1 = b2 ? acc[1] : acc[3];
-  const float h0 = keep0 + (IN_REGISTERS ? lane_xor4(send0) : __shfl_xor(send0, 4));
-  const float h1 = keep1 + (IN_REGISTERS ? lane_xor4(send1) : __shfl_xor(send1, 4));
+  const float h0 = keep0 + __shfl_xor(send0, 4);
+  const float h1 = keep1 + __shfl_xor(send1, 4);
   const float keep = b3 ? h1 : h0, send = b3 ? h0 : h1;
   const float s = keep + dpp_f32<kDppRowRor8>(send);
-  return IN_REGISTERS ? sum_lane_xor16(s) : s + __shfl_xor(s, 16);
+  return s + __shfl_xor(s, 16);
 }
 
 // The lookups of one (plane, row-of-four) step: the four dwords' key bytes, one 16-byte read each.
