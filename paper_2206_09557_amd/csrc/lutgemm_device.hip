@@ -196,17 +196,30 @@ __device__ __forceinline__ float quad_rows_reduce(const float (&acc)[4], int lan
 //   kAlphaPerSlot  one fetch per dword (slot); the two chunks of a slot share a group
 //                  (g % 16 == 0, or T == 1).
 //   kAlphaPerChunk one fetch per (dword, sub-slab): g % 16 != 0 with T == 2.
+//   kAlphaSlotPair one fetch per pair of slots (g % 32 == 0 with T == 2: slots 2P and 2P + 1
+//                  are 32 columns of one group).  Which of a lane's dwords make a pair depends
+//                  on the lane (its dword s holds slot (s + k) mod 4 of the quad): dwords
+//                  (0, 1) and (2, 3) in the lanes with even k, (0, 3) and (1, 2) with odd k.
+//                  So the odd lanes take their dwords in the order 0, 3, 2, 1 (dword_of):
+//                  every per-lane constant is computed in that order, and the fetched key
+//                  words have dwords 1 and 3 exchanged by two selects before the lookups.
 // Added to any of them, kAlphaShared says that the scale buffer holds ONE value per (row,
 // group), alpha_0, and that plane i has the scale 2^i * alpha_0 (appendix C: the scales of
 // uniformly quantised weights): one fetch of four rows instead of four rows x q planes.
-enum { kAlphaQuad = 0, kAlphaPerSlot = 1, kAlphaPerChunk = 2, kAlphaShared = 4 };
+enum { kAlphaQuad = 0, kAlphaPerSlot = 1, kAlphaPerChunk = 2, kAlphaSlotPair = 3, kAlphaShared = 4 };
+
+// The s-th dword a lane works on, as an index into its fetched key words.
+template <int AMODE>
+__device__ __forceinline__ int dword_of(int s, int lane) {
+  return ((AMODE & 3) == kAlphaSlotPair && (lane & 1)) ? ((4 - s) & 3) : s;
+}
 
 // What one wavefront fetches for planes I0 .. I0+QP-1 of one (K tile, row block) unit of a
 // Q-plane layer.  (Layers of up to four planes are fetched whole; more planes go in two
 // halves so that a wavefront never needs more registers than it has.)
 template <int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
 struct Unit {
-  static constexpr int NS = ((AMODE & 3) == kAlphaQuad) ? 1 : 4;                 // scale sets along the dwords
+  static constexpr int NS = ((AMODE & 3) == kAlphaQuad) ? 1 : ((AMODE & 3) == kAlphaSlotPair ? 2 : 4);   // scale sets along the dwords
   static constexpr int NC = ((AMODE & 3) == kAlphaPerChunk) ? T : 1;             // ... and along the sub-slabs
   u32x4 w[QP][T];           // key words: dword s = four rows of slot 4j + (s + k) mod 4
   u32x2 al[NS][NC][QP];     // fp16 scales of the lane's four rows
@@ -215,11 +228,11 @@ struct Unit {
 };
 
 // Group index of every (dword, sub-slab) of this lane in tile kt.
-template <int T, bool SHIFT = true>
+template <int T, bool SHIFT = true, int AMODE = kAlphaQuad>
 __device__ __forceinline__ void lane_groups(const GemvParams& p, int kt, int lane, int chunks_in_tile, int (&grp)[4][T]) {
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    const int slot = (lane & ~3) | ((s + lane) & 3);
+    const int slot = (lane & ~3) | ((dword_of<AMODE>(s, lane) + lane) & 3);
 #pragma unroll
     for (int t = 0; t < T; ++t) {
       const int cc = min(T * slot + t, chunks_in_tile - 1);
@@ -248,7 +261,7 @@ __device__ __forceinline__ void load_unit(Unit<Q, I0, QP, T, AMODE, HAS_Z>& u, c
   for (int s = 0; s < U::NS; ++s)
 #pragma unroll
     for (int c = 0; c < U::NC; ++c) {
-      const int64_t blk = (int64_t)rb * p.NG + grp[s][c];
+      const int64_t blk = (int64_t)rb * p.NG + grp[s * (4 / U::NS) % 4][c];   // first dword of the set
       if ((AMODE & kAlphaShared) != 0) {   // one scale per (row, group), laid out like the offsets
         u.al[s][c][0] = *reinterpret_cast<const u32x2*>(p.alpha + blk * 16 + (lane & 3) * 4);
       } else {
@@ -284,8 +297,18 @@ __device__ __forceinline__ void accumulate_unit(const Unit<Q, I0, QP, T, AMODE, 
                                                 const uint32_t (&lane_base)[4], const float (&sum_x)[4][T],
                                                 float (&acc)[4]) {
   using U = Unit<Q, I0, QP, T, AMODE, HAS_Z>;
+  constexpr bool kPairs = (AMODE & 3) == kAlphaSlotPair;
+  const bool odd = kPairs && ((lane_base[0] >> 2) & 1u) != 0;   // k of the lane: its first slot is 4j + k
 #pragma unroll
   for (int i = 0; i < QP; ++i) {
+    uint32_t kw[T][4];   // the key words in the lane's dword order
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      kw[t][0] = u.w[i][t][0];
+      kw[t][1] = odd ? u.w[i][t][3] : u.w[i][t][1];
+      kw[t][2] = u.w[i][t][2];
+      kw[t][3] = odd ? u.w[i][t][1] : u.w[i][t][3];
+    }
 #pragma unroll
     for (int rho = 0; rho < 4; ++rho) {
       // address bytes {0, t, key byte rho, slot * 4}: byte 1 of lane_base is the constant 1
@@ -296,13 +319,14 @@ __device__ __forceinline__ void accumulate_unit(const Unit<Q, I0, QP, T, AMODE, 
       for (int s = 0; s < 4; ++s) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-          const float v = lds_f32(__builtin_amdgcn_perm(u.w[i][t][s], lane_base[s], sel_t[t]));
+          const float v = lds_f32(__builtin_amdgcn_perm(kw[t][s], lane_base[s], sel_t[t]));
           run = run_open ? run + v : v;
           run_open = true;
           const bool close = ((AMODE & 3) == kAlphaPerChunk) || ((AMODE & 3) == kAlphaPerSlot && t == T - 1) ||
-                             (s == 3 && t == T - 1);
+                             (kPairs && (s & 1) && t == T - 1) || (s == 3 && t == T - 1);
           if (close) {
-            const int ss = ((AMODE & 3) == kAlphaQuad) ? 0 : s, cc = ((AMODE & 3) == kAlphaPerChunk) ? t : 0;
+            const int ss = ((AMODE & 3) == kAlphaQuad) ? 0 : (kPairs ? s >> 1 : s);
+            const int cc = ((AMODE & 3) == kAlphaPerChunk) ? t : 0;
             acc[rho] = fmaf(scale_of<AMODE>(u.al[ss][cc], i, I0 + i, rho), run, acc[rho]);
             run_open = false;
           }
@@ -324,6 +348,12 @@ __device__ __forceinline__ void accumulate_unit(const Unit<Q, I0, QP, T, AMODE, 
             for (int t = 0; t < T; ++t) sx += sum_x[s2][t];
         } else if ((AMODE & 3) == kAlphaPerSlot) {
           sx = (T == 2) ? sum_x[s][0] + sum_x[s][T - 1] : sum_x[s][0];
+        } else if (kPairs) {
+          sx = 0.0f;
+#pragma unroll
+          for (int s2 = 2 * s; s2 < 2 * s + 2; ++s2)
+#pragma unroll
+            for (int t = 0; t < T; ++t) sx += sum_x[s2][t];
         } else {
           sx = sum_x[s][c];
         }
@@ -402,11 +432,11 @@ __device__ __forceinline__ int next_unit(float* lut, int lane) {
 // Per-lane lookup constants: dword s of this lane looks into the table of slot
 // 4j + (s + k) mod 4.  lane_base byte 0: slot * 4; byte 1: the constant 1 (source of the
 // sub-slab address bit).  sum_x: entry 0xFF of each table = the sum of its 8 activations.
-template <int T, bool HAS_Z>
+template <int T, bool HAS_Z, int AMODE = kAlphaQuad>
 __device__ __forceinline__ void lane_tables(int lane, uint32_t (&lane_base)[4], float (&sum_x)[4][T]) {
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    const uint32_t slot = ((uint32_t)lane & ~3u) | ((uint32_t)(s + lane) & 3u);
+    const uint32_t slot = ((uint32_t)lane & ~3u) | ((uint32_t)(dword_of<AMODE>(s, lane) + lane) & 3u);
     lane_base[s] = (slot << 2) | 0x100u;
 #pragma unroll
     for (int t = 0; t < T; ++t)
@@ -469,7 +499,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
 
   int grp[4][T];
   // (the per-chunk scale mode has no registers to spare for the two code paths of the shift)
-  lane_groups<T, (AMODE & 3) != kAlphaPerChunk>(p, kt, lane, chunks_in_tile, grp);
+  lane_groups<T, (AMODE & 3) != kAlphaPerChunk, AMODE>(p, kt, lane, chunks_in_tile, grp);
   // the row of the 16-row block whose sum this lane ends up with (see quad_rows_reduce)
   const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
 
@@ -483,7 +513,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
     __syncthreads();
     uint32_t lane_base[4];
     float sum_x[4][T];
-    lane_tables<T, HAS_Z>(lane, lane_base, sum_x);
+    lane_tables<T, HAS_Z, AMODE>(lane, lane_base, sum_x);
     for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
       float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
       float prev = 0.0f;
@@ -506,7 +536,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   U u;
   int cur = wave;                               // unit being computed (or about to be)
   // kEarly: the common scale mode, which has the registers for the fetch code twice.
-  constexpr bool kEarly = AMODE == kAlphaQuad;
+  constexpr bool kEarly = AMODE == kAlphaQuad || AMODE == kAlphaSlotPair;
   if (kEarly) {
     // Two roles at the start of a tile.  Wavefronts 8..15 build the tables, two slots each.
     // Wavefronts 0..7 ask for their first unit meanwhile, but not before the builders HAVE
@@ -541,7 +571,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   }
   uint32_t lane_base[4];
   float sum_x[4][T];
-  lane_tables<T, HAS_Z>(lane, lane_base, sum_x);
+  lane_tables<T, HAS_Z, AMODE>(lane, lane_base, sum_x);
 
   // ---- lookup / accumulate ----
   // Up to four results are parked in ONE register (the j-th of a trip in lanes 16j..16j+15)
@@ -1183,7 +1213,7 @@ GemvKernel pick_q(int q) {
 template <bool HAS_Z, int SH>
 GemvKernel pick_mode(int q, int64_t g) {
   if (g % 64 == 0) return pick_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
-  if (g % 32 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
+  if (g % 32 == 0) return pick_q<HAS_Z, kAlphaSlotPair | SH, kAlphaQuad | SH>(q);
   if (g % 16 == 0) return pick_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
   return pick_q<HAS_Z, kAlphaPerChunk | SH, kAlphaPerSlot | SH>(q);
 }
@@ -1212,7 +1242,7 @@ GemvKernel pick_group_q(int q) {
 template <bool HAS_Z, int SH>
 GemvKernel pick_group_mode(int q, int64_t g) {   // as pick_mode, without the register-bound scale set per chunk
   if (g % 64 == 0) return pick_group_q<HAS_Z, kAlphaQuad | SH, kAlphaQuad | SH>(q);
-  if (g % 32 == 0) return pick_group_q<HAS_Z, kAlphaPerSlot | SH, kAlphaQuad | SH>(q);
+  if (g % 32 == 0) return pick_group_q<HAS_Z, kAlphaSlotPair | SH, kAlphaQuad | SH>(q);
   if (g % 16 == 0) return pick_group_q<HAS_Z, kAlphaPerSlot | SH, kAlphaPerSlot | SH>(q);
   return nullptr;
 }
