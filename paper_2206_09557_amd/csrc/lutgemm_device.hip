@@ -3,9 +3,11 @@
 // (paper section 3.1, section 3.2, appendix B), behind lutgemm_gemv / lutgemm_gemm.
 //
 // Mapping (this library's own; the paper's thread-block design was made for another GPU):
-//   * One workgroup of 16 wavefronts owns one K tile (1024 input columns = 128 tables
-//     of 256 fp32 entries = 128 KB of LDS) for a contiguous range of row blocks, so a
-//     table set is built once per workgroup and reused for thousands of rows.
+//   * One workgroup of 16 wavefronts owns a K group (one or a few consecutive K tiles; a
+//     tile is 1024 input columns = 128 tables of 256 fp32 entries = 128 KB of LDS) for a
+//     contiguous range of row blocks, so a table set is built once per workgroup and tile
+//     and reused for hundreds to thousands of rows; with several tiles the row sums stay
+//     in LDS from tile to tile.
 //   * Table (t, L) lives at LDS byte address  t<<16 | key<<8 | L<<2 : its 256 entries all
 //     sit in bank L, and the address of a lookup is one byte permute of the packed key word.
 //   * Inside a quad of lanes the rows are dealt out (lane k owns rows 4k..4k+3 of the
