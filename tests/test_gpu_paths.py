@@ -172,3 +172,45 @@ def test_plan_grid_reports_what_is_launched():
             assert kg * rs <= max(cus, kg)
     assert L.lutgemm_plan_grid(*synth.OPT_175B["fc2"], 3, 128, 1)[1] > 1
     assert L.lutgemm_plan_grid(*synth.OPT_175B["out"], 3, 128, 1)[1] == 1
+
+
+@pytest.mark.parametrize("m,n,q,g,batch", [(4096, 16384, 3, 128, 1), (2048, 32768, 3, 128, 1), (4096, 16384, 3, 128, 4)])
+def test_split_k_hand_off_over_many_launches(m, n, q, g, batch):
+    """The cross-group reduction (partials, arrival counter, last workgroup sums) must give the
+    same bits on every one of several hundred back-to-back launches that share one workspace,
+    while another stream keeps the memory system busy, and those bits must be the oracle's."""
+    from gpu_util import make_workspace, torch_cuda
+    torch = torch_cuda()
+    kg, tpg, rs = L.lutgemm_plan_grid(m, n, q, g, batch)
+    print(f"case hand-off m={m} n={n} q={q} g={g} batch={batch}: grid KG={kg} TPG={tpg} RS={rs}", flush=True)
+    assert kg > 1, "this shape is meant to have several K groups"
+    W = synth.weights_fp16(m, n, seed=13000 + n + batch)
+    p = Packed.from_weights(W, q, g)
+    del W
+    X = np.stack([synth.activations_fp16(n, seed=13500 + b) for b in range(batch)])
+    x = X[0] if batch == 1 else X
+    y_first = _check_all_rows(p, x)
+
+    launches = 300
+    d_x = torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).cuda()
+    d_y = torch.full((launches, batch, m), float("nan"), dtype=torch.float32, device="cuda")
+    wsb = L.lutgemm_workspace_bytes(m, n, q, g, 8, batch)
+    d_ws = make_workspace(wsb)
+    side = torch.cuda.Stream()
+    a = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    s = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+    for i in range(launches):
+        if i % 10 == 0:
+            with torch.cuda.stream(side):
+                b.copy_(a, non_blocking=True)
+        if batch == 1:
+            L.lutgemm_gemv(d_x, p.d_bits, p.d_alpha, p.d_z, d_y[i], q, g, 8, m, n, L.LUTGEMM_Y_F32, d_ws, wsb, s.cuda_stream)
+        else:
+            L.lutgemm_gemm(d_x, p.d_bits, p.d_alpha, p.d_z, d_y[i], q, g, 8, m, n, batch, L.LUTGEMM_Y_F32, d_ws, wsb,
+                           s.cuda_stream)
+    torch.cuda.synchronize()
+    want = torch.from_numpy(np.ascontiguousarray(y_first).reshape(1, batch, m)).cuda()
+    same = (d_y == want).all(dim=2).all(dim=1)
+    assert bool(same.all()), f"launches that differ from the first: {(~same).nonzero().flatten().tolist()[:10]}"
