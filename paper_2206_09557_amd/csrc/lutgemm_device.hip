@@ -1370,9 +1370,16 @@ bool carries_in_lds(int q, int64_t g) { return q <= 4 && g % 16 == 0; }
 // With the running sums of a K group in LDS, two tiles per group beat one on the tall layers
 // with 12 tiles (36864 and 49152 rows x 12288: 6 groups instead of 12), three beat one on
 // 12288 x 49152; the small layers keep one tile per group.
+// Most row ranges the GEMV kernel is given: at least eight units per workgroup.  (Layers too
+// small to give every compute unit sixteen run faster on twice the workgroups with half the
+// wavefronts fetching, the builders of the tile start only building: 5120 x 5120 at q = 4
+// 9.6 -> 8.8 us, 4096 x 4096 8.0 -> 7.1, 1024 x 1024 5.6 -> 5.0; four units per workgroup
+// are faster still below 2048 x 2048 and slower above.)
+inline int max_row_ranges(int RB) { return (RB + kWaves / 2 - 1) / (kWaves / 2); }
+
 void choose_grid(int cus, int NT, int RB, bool lds_carry, int* KG, int* TPG, int* RS) {
   double best = 1e30;
-  const int max_rs = (RB + kWaves - 1) / kWaves;
+  const int max_rs = max_row_ranges(RB);
   for (int tpg = 1; tpg <= NT && tpg <= 8; ++tpg) {
     const int kg = (NT + tpg - 1) / tpg;
     int rs = cus / kg;
@@ -1440,7 +1447,7 @@ void plan_grid(int cus, int vectors, int q, int64_t g, GemvParams* p) {
   const int which = vectors == 4 ? 2 : (vectors == 2 ? 1 : 0);
   const int tpg = tuning().tpg[which], rs = tuning().rs[which];
   const int row_units = vectors == 4 ? (p->RB + 1) / 2 : p->RB;
-  const int max_rs = (row_units + kWaves - 1) / kWaves;
+  const int max_rs = vectors == 1 ? max_row_ranges(row_units) : (row_units + kWaves - 1) / kWaves;
   if (tpg > 0) {
     p->TPG = tpg > p->NT ? p->NT : tpg;
     p->KG = (p->NT + p->TPG - 1) / p->TPG;
