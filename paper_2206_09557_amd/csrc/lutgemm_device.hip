@@ -538,7 +538,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   U u;
   int cur = wave;                               // unit being computed (or about to be)
   // kEarly: the common scale mode, which has the registers for the fetch code twice.
-  constexpr bool kEarly = AMODE == kAlphaQuad || AMODE == kAlphaSlotPair;
+  constexpr bool kEarly = (AMODE & 3) == kAlphaQuad || (AMODE & 3) == kAlphaSlotPair;
   if (kEarly) {
     // Two roles at the start of a tile.  Wavefronts 8..15 build the tables, two slots each.
     // Wavefronts 0..7 ask for their first unit meanwhile, but not before the builders HAVE
