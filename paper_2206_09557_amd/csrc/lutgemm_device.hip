@@ -217,8 +217,9 @@ __device__ __forceinline__ int dword_of(int s, int lane) {
 }
 
 // What one wavefront fetches for planes I0 .. I0+QP-1 of one (K tile, row block) unit of a
-// Q-plane layer.  (Layers of up to four planes are fetched whole; more planes go in two
-// halves so that a wavefront never needs more registers than it has.)
+// Q-plane layer.  (The GEMV kernel fetches all planes of a unit at once, except one plane at
+// a time where every chunk has a scale set of its own; the pair and quad kernels, whose
+// lookups need more registers, fetch layers of more than four planes in two or three parts.)
 template <int Q, int I0, int QP, int T, int AMODE, bool HAS_Z>
 struct Unit {
   static constexpr int NS = ((AMODE & 3) == kAlphaQuad) ? 1 : ((AMODE & 3) == kAlphaSlotPair ? 2 : 4);   // scale sets along the dwords
@@ -505,10 +506,11 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   // the row of the 16-row block whose sum this lane ends up with (see quad_rows_reduce)
   const int out_row = 4 * (lane & 3) + ((lane & 4) ? 2 : 0) + ((lane & 8) ? 1 : 0);
 
-  // Planes fetched together: all of them for up to four planes, about half for more; one
-  // at a time when every (dword, sub-slab) has a scale set of its own.  Keeps a wavefront
-  // within its registers in every variant.
-  constexpr int PP = ((AMODE & 3) == kAlphaPerChunk) ? 1 : (Q > 4 ? (Q + 1) / 2 : Q);
+  // Planes fetched together: all of them (up to 8 x 2 x 4 registers of key words: measured 2
+  // to 15 % faster than two halves for five to eight planes); one at a time when every
+  // (dword, sub-slab) has a scale set of its own.  Keeps a wavefront within its registers in
+  // every variant.
+  constexpr int PP = ((AMODE & 3) == kAlphaPerChunk) ? 1 : Q;
   if constexpr (PP < Q) {
     // ---- several fetches per unit, no fetch-ahead ----
     build_slot<T>(lut, chunks_in_tile, wave, lane, fetch_slot_x<T>(p, kt, chunks_in_tile, wave, lane));
@@ -519,7 +521,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
     for (int rb = rb0 + wave; rb < rb1; rb += kWaves) {
       float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
       float prev = 0.0f;
-      // (these register-bound variants have no room for running sums in LDS: the sum of the
+      // (this register-bound variant has no running sums in LDS: the sum of the
       // K group's earlier tiles comes back from the workspace with the first fetch of a unit,
       // always in the wavefront that wrote it, and the new sum goes there again)
       plane_passes<Q, 0, PP, T, AMODE, HAS_Z>(p, tile_base, rb, lane, grp, partial, out_row, !first_tile, lane_base, sum_x,
@@ -537,8 +539,9 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
   if (threadIdx.x == 0) reinterpret_cast<int*>(lut + kQueueWord)[0] = kWaves;   // units 0..kWaves-1 are taken
   U u;
   int cur = wave;                               // unit being computed (or about to be)
-  // kEarly: the common scale mode, which has the registers for the fetch code twice.
-  constexpr bool kEarly = (AMODE & 3) == kAlphaQuad || (AMODE & 3) == kAlphaSlotPair;
+  // kEarly: the scale modes with one or two scale sets per lane, which have the registers for
+  // the fetch code twice (all but eight planes with offsets and two scale sets).
+  constexpr bool kEarly = (AMODE & 3) == kAlphaQuad || ((AMODE & 3) == kAlphaSlotPair && !(Q == 8 && HAS_Z));
   if (kEarly) {
     // Two roles at the start of a tile.  Wavefronts 8..15 build the tables, two slots each.
     // Wavefronts 0..7 ask for their first unit meanwhile, but not before the builders HAVE
@@ -603,7 +606,7 @@ __device__ __forceinline__ void tile_body(const GemvParams& p, float* lut, int k
         store_row_sum(p, partial, direct, parked_rb * 16 + out_row, parked);
     }
   }
-  }   // Q <= 4
+  }   // PP == Q
 }
 
 // Sum over the K groups and store for rows [rb0 * 16, row_end): RPP rows per thread per pass,
@@ -778,7 +781,7 @@ __device__ __forceinline__ void gemv_workgroup(const GemvParams& p, float* lut, 
   const int kt_end = min((kg + 1) * p.TPG, p.NT);
   // several tiles per K group: running sums in LDS (see carries_in_lds; a last K group with a
   // single tile takes the same path as the others)
-  constexpr bool kCarry = Q <= 4 && (AM2 & 3) != kAlphaPerChunk;
+  constexpr bool kCarry = (AM2 & 3) != kAlphaPerChunk;
   const bool carry = kCarry && p.TPG > 1;
 
   for (int kt = kg * p.TPG; kt < kt_end; ++kt) {
@@ -1353,9 +1356,9 @@ const Tuning& tuning() {
 
 // How the GEMV kernel of a (q, g) layer carries row sums from tile to tile of a K group: the
 // variants that fetch a unit in one piece keep them in LDS, which bounds the row range of a
-// workgroup; the register-bound ones (more than four planes, or a scale set per chunk:
-// g % 16 != 0) send them through the workspace.
-bool carries_in_lds(int q, int64_t g) { return q <= 4 && g % 16 == 0; }
+// workgroup; the register-bound one (a scale set per chunk: g % 16 != 0) sends them through
+// the workspace.
+bool carries_in_lds(int64_t g) { return g % 16 == 0; }
 
 // Workgroup grid: KG groups of TPG consecutive K tiles times row_splits row ranges, one
 // workgroup per compute unit.  Cost model in units of one round of units of a workgroup (16
@@ -1437,7 +1440,7 @@ void choose_vector_grid(int vectors, int cus, int NT, int row_units, int* KG, in
 // vectors: 1 (GEMV kernel), 2 (pair kernel), 4 (quad kernel)
 void plan_grid(int cus, int vectors, int q, int64_t g, GemvParams* p) {
   const int wgs = cus > 256 ? 256 : cus;
-  const bool lds_carry = carries_in_lds(q, g);
+  const bool lds_carry = carries_in_lds(g);
   if (vectors == 4)
     choose_vector_grid(4, wgs, p->NT, (p->RB + 1) / 2, &p->KG, &p->TPG, &p->row_splits);
   else if (vectors == 2)
@@ -1700,7 +1703,7 @@ int lutgemm_gemm(const void* x, const void* bits, const void* alpha, const void*
 
   GemvKernel kern = pick_kernel(q, z != nullptr, shared, gg);
   if (!kern) return LUTGEMM_EUNSUPPORTED;
-  if (p.TPG > 1 && carries_in_lds(q, gg) && (p.RB + p.row_splits - 1) / p.row_splits > kRunBlocks)
+  if (p.TPG > 1 && carries_in_lds(gg) && (p.RB + p.row_splits - 1) / p.row_splits > kRunBlocks)
     return LUTGEMM_EUNSUPPORTED;   // (never planned: the kernel's running sums would not fit)
 
   uint32_t* counters = static_cast<uint32_t*>(workspace);
@@ -1919,7 +1922,7 @@ int lutgemm_gemv_group(const void* const* x, const void* const* bits, const void
     p.y_f32 = (flags & LUTGEMM_Y_F32) ? 1 : 0;
     p.batch = 1;
     plan_grid(cus, 1, q, gg, &p);
-    if (p.TPG > 1 && carries_in_lds(q, gg) && (p.RB + p.row_splits - 1) / p.row_splits > kRunBlocks)
+    if (p.TPG > 1 && carries_in_lds(gg) && (p.RB + p.row_splits - 1) / p.row_splits > kRunBlocks)
       return LUTGEMM_EUNSUPPORTED;   // (never planned)
     if (p.row_splits > 256) return LUTGEMM_EUNSUPPORTED;   // 256 arrival counters per layer
     const int64_t m_pad = (int64_t)(p.RB + (p.RB & 1)) * 16;

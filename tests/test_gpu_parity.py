@@ -245,7 +245,7 @@ SHARED_CASES = [
     (300, 2048, 2, 64, None),
     (1000, 1536, 4, 128, None),   # last tile with one sub-slab
     (96, 1048, 3, 8, None),       # per-chunk scale fetches, ragged tile
-    (130, 1032, 5, 24, None),     # more than four planes (fetched in two halves)
+    (130, 1032, 5, 24, None),     # more than four planes, a scale set per chunk (fetched plane by plane)
     (77, 520, 8, 0, None),        # row-wise, eight planes
     (4100, 3072, 3, 128, 5),      # batch: pairs and an odd last vector
     (333, 2048, 4, 32, 2),

@@ -48,11 +48,11 @@ def _check_all_rows(p, x, shared=False):
 GEMV_CASES = [
     (48, 131072, 3, 128, "greedy", False),     # the plain case
     (48, 131072, 3, 128, "rtn", False),        # offsets (eq. 3) carried across tiles
-    (48, 131072, 5, 128, "greedy_z", False),   # more than four planes: fetched in two halves
+    (48, 131072, 5, 128, "greedy_z", False),   # more than four planes
     (33, 131072, 8, 0, "greedy", False),       # eight planes, row-wise scales, ragged rows
     (48, 131072, 3, 32, "rtn", False),         # one scale set per pair of slots
     (48, 147456, 4, 96, "greedy_z", False),    # ... with groups of 96 columns, which straddle K tiles
-    (48, 131872, 5, 32, "rtn", False),         # ... planes in two halves, last tile of 100 chunks
+    (48, 131872, 5, 32, "rtn", False),         # ... five planes, last tile of 100 chunks
     (48, 131072, 2, 32, "rtn", True),          # ... shared-scale layout
     (48, 131072, 3, 16, "rtn", False),         # one scale set per slot
     (48, 147456, 2, 24, "greedy_z", False),    # g = 8 * 3: one scale set per chunk
