@@ -367,6 +367,45 @@ def test_random_wide_shapes_small_batch(m, n, q, g, mode, batch):
         np.testing.assert_array_equal(run(p, X, f32_out=True, shared=True), y)
 
 
+def _random_wide_gemv_cases(count, seed):
+    """Long rows at batch 1: K groups of several tiles in the GEMV kernel with every plane count
+    and every scale mode, group sizes that are odd multiples of 32 columns among them (one scale
+    set per pair of slots), ragged last tiles of either kind."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        q = int(rng.integers(1, 9))
+        g_units = int(rng.choice([1, 2, 3, 4, 4, 8, 12, 12, 16, 20, 24]))
+        m = int(rng.integers(1, 100)) if rng.random() < 0.6 else int(rng.integers(100, 900))
+        groups = int(rng.integers(40, 6000))
+        n = 8 * g_units * groups
+        if n < 6144 or n > (300000 if m < 100 else 70000):   # few rows, very long: several tiles per K group
+            continue
+        g = 0 if rng.random() < 0.1 else 8 * g_units
+        mode = ["greedy", "greedy_z", "rtn"][int(rng.integers(0, 3))]
+        cases.append((m, n, q, g, mode))
+    return cases
+
+
+@pytest.mark.parametrize("m,n,q,g,mode", _random_wide_gemv_cases(20, 20240613))
+def test_random_wide_shapes_gemv(m, n, q, g, mode):
+    print(f"case wide gemv m={m} n={n} q={q} g={g} mode={mode} grid (KG, TPG, RS) {L.lutgemm_plan_grid(m, n, q, g, 1)}",
+          flush=True)
+    W = synth.weights_fp16(m, n, seed=9700 + m + 3 * n + q)
+    x = synth.activations_fp16(n, seed=9800 + m + n)
+    p = Packed.from_weights(W, q, g, MODES[mode])
+    del W
+    bound = _bound(p)
+    y_ref, _ = c_oracle.gemv_packed(p.bits, p.alpha, p.z, x[None, :], p.m, p.n, p.q, p.g)
+    y = run(p, x, f32_out=True)
+    check_parity(y, y_ref[0], x, bound, f32_out=True)
+    check_parity(run(p, x), y_ref[0], x, bound)
+    np.testing.assert_array_equal(run(p, x, f32_out=True), y)    # bitwise reproducible
+    if mode == "rtn":                      # shared-scale layout: bitwise the same as per-plane scales
+        p.share()
+        np.testing.assert_array_equal(run(p, x, f32_out=True, shared=True), y)
+
+
 @pytest.mark.parametrize("m,n,q,g,batch", [
     (16, 262144, 2, 128, None),     # one row block, 256 K tiles: deep split-K
     (40, 65536, 3, 1024, 4),        # few rows, long rows, four vectors
